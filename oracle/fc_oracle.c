@@ -1,0 +1,322 @@
+/*
+ * fc_oracle.c -- plain CPU oracle for the Flash Communication quantization
+ * arithmetic (arXiv 2412.04964).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is a slow, scalar,
+ * one-element-at-a-time statement of what the GPU library must compute and it
+ * shares nothing with the HIP sources: no header, no helper, no table.  Only
+ * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What it follows in the paper
+ *   - asymmetric group quantizer: Appendix "Quantization Fundamentals",
+ *     Eq. 1 (scale, zero-point) and Eq. 2 (codes, clamp to [0, 2^n-1]);
+ *   - two-step all-reduce: Algorithm 1 (FinegrainedQuantize -> exchange ->
+ *     Dequantize each of the N slices -> ReduceSum -> FinegrainedQuantize ->
+ *     exchange -> Dequantize), Section 3.2.2;
+ *   - groups run along the hidden dimension of one token (Section 3.2.1,
+ *     the block-size figure: 4096 = hidden down to 128);
+ *   - mixed bit-widths ("INT6" = 4-bit before the reduce, 8-bit before the
+ *     gather): Section 3.2.3, "INT6 Quantization".
+ *
+ * Readings taken where the paper is silent or garbled (every one of them is a
+ * plain fp32 operation in the order written below, default rounding mode):
+ *   R1  the rounding bracket of Eq. 1-2 is round-to-nearest, ties to even;
+ *   R2  Dequantize, which the paper calls but never prints, is the inverse of
+ *       Eq. 2:  x^ = (q - z) * s;
+ *   R3  s and z are stored as fp32; z is integer-valued and is NOT clamped;
+ *   R4  X/s is evaluated as X * (1/s) with one reciprocal per group, and the
+ *       zero-point uses the same product, so the group minimum always gets
+ *       code 0;
+ *   R5  a group whose range is zero (or so small that s would be subnormal)
+ *       takes s = |min| (1 if that is below FLT_MIN too): all codes are 0 and
+ *       a constant group reconstructs exactly;
+ *   R6  the N-way sum is an fp32 fused-multiply-add chain over the sources in
+ *       index order, starting from +0;
+ *   R7  Algorithm 1's Dequantize takes each slice's own scale (the symbol is
+ *       dropped in the listing) and the sum has N terms;
+ *   R8  INT4 codes are packed two per byte in linear order, element 2k in the
+ *       low nibble and element 2k+1 in the high nibble.
+ * Domain: finite inputs.  NaN / Inf inputs: parity unpinned.
+ *
+ * Build: cc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
+ *        (contraction must stay off: every product and sum below is rounded
+ *        on its own, except the explicit fmaf of R6).
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define FC_REF_OK 0
+#define FC_REF_BAD_ARG (-1)
+#define FC_REF_NO_MEM (-2)
+
+/* ------------------------------------------------------------------------ */
+/* IEEE binary16 <-> binary32, written out on the bit fields (1 sign, 5      */
+/* exponent bits with bias 15, 10 fraction bits: Appendix, "IEEE 754         */
+/* standards for FP16").                                                     */
+/* ------------------------------------------------------------------------ */
+
+float fc_ref_half_to_float(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int e = (h >> 10) & 0x1F;
+    const int f = h & 0x3FF;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);               /* zero or subnormal: f * 2^-24 */
+    else if (e == 31)
+        v = f ? (double)NAN : (double)INFINITY;
+    else
+        v = ldexp((double)(1024 + f), e - 25);   /* (1 + f/1024) * 2^(e-15) */
+    return (float)(sign ? -v : v);               /* every binary16 is exact in binary32 */
+}
+
+/* Round-to-nearest-even conversion; overflow goes to infinity. */
+uint16_t fc_ref_float_to_half(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    if (isnan(x)) return (uint16_t)(sign | 0x7E00u);
+    const double a = fabs((double)x);
+    if (a == 0.0) return sign;
+    if (isinf(x)) return (uint16_t)(sign | 0x7C00u);
+    int e2;
+    (void)frexp(a, &e2);                         /* a = m * 2^e2, m in [0.5, 1) */
+    int e = e2 - 1;                              /* a in [2^e, 2^(e+1)) */
+    if (e < -14) e = -14;                        /* subnormal range shares the 2^-24 grid */
+    /* spacing of binary16 numbers around a is 2^(e-10); a / spacing is exact
+       in double, nearbyint rounds half to even in the default mode */
+    const double n = nearbyint(ldexp(a, 10 - e));
+    uint32_t mant = (uint32_t)n;                 /* in [0, 2048] */
+    int be = e + 15;                             /* biased exponent when mant >= 1024 */
+    if (mant >= 2048u) { mant = 1024u; be += 1; }
+    if (mant < 1024u) return (uint16_t)(sign | mant);           /* subnormal (or zero) */
+    if (be >= 31) return (uint16_t)(sign | 0x7C00u);            /* overflow */
+    return (uint16_t)(sign | ((uint32_t)be << 10) | (mant - 1024u));
+}
+
+/* ------------------------------------------------------------------------ */
+/* FinegrainedQuantize of ONE group (Eq. 1-2 under R1, R3, R4, R5).          */
+/* x: g fp32 values.  q: g codes, one per byte (not packed).                 */
+/* ------------------------------------------------------------------------ */
+
+void fc_ref_quantize_group_f32(const float *x, int g, int bits,
+                               uint8_t *q, float *scale, float *zero)
+{
+    const float qmax = (float)((1 << bits) - 1);
+    float mn = x[0], mx = x[0];
+    for (int k = 1; k < g; ++k) {
+        if (x[k] < mn) mn = x[k];
+        if (x[k] > mx) mx = x[k];
+    }
+    const float r = mx - mn;
+    float s = r / qmax;                          /* Eq. 1, scale */
+    if (!(s >= FLT_MIN)) {                       /* R5: degenerate range */
+        const float a = fabsf(mn);
+        s = (a >= FLT_MIN) ? a : 1.0f;
+    }
+    const float inv = 1.0f / s;                  /* R4 */
+    const float zf = 0.0f - rintf(mn * inv);     /* Eq. 1, zero-point; 0 - (-0) = +0 */
+    for (int k = 0; k < g; ++k) {
+        const float t = rintf(x[k] * inv);       /* Eq. 2: round(X / s) */
+        float u = t + zf;                        /*        + z          */
+        if (u < 0.0f) u = 0.0f;                  /*        clamp        */
+        if (u > qmax) u = qmax;
+        q[k] = (uint8_t)u;
+    }
+    *scale = s;
+    *zero = zf;
+}
+
+static int check_shape(int64_t tokens, int64_t hidden, int group, int bits)
+{
+    if (tokens < 0 || hidden <= 0 || group <= 0) return 0;
+    if (bits != 4 && bits != 8) return 0;
+    if (hidden % group != 0) return 0;
+    if (bits == 4 && (hidden % 2) != 0) return 0;
+    return 1;
+}
+
+/* store one row of codes: one byte each (8 bit) or two per byte (R8) */
+static void pack_row(const uint8_t *q, int64_t hidden, int bits, uint8_t *dst)
+{
+    if (bits == 8) {
+        memcpy(dst, q, (size_t)hidden);
+    } else {
+        for (int64_t k = 0; k < hidden / 2; ++k)
+            dst[k] = (uint8_t)(q[2 * k] | (q[2 * k + 1] << 4));
+    }
+}
+
+static unsigned code_at(const uint8_t *row, int64_t h, int bits)
+{
+    if (bits == 8) return row[h];
+    const uint8_t b = row[h / 2];
+    return (h & 1) ? (unsigned)(b >> 4) : (unsigned)(b & 0x0F);
+}
+
+/* FinegrainedQuantize of an fp32 matrix [tokens, hidden], groups along hidden. */
+int fc_ref_quantize_f32(const float *x, int64_t tokens, int64_t hidden, int group, int bits,
+                        uint8_t *codes, float *scales, float *zeros)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x || !codes || !scales || !zeros) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;          /* groups per row */
+    const int64_t row_bytes = hidden * bits / 8;
+    uint8_t *q = (uint8_t *)malloc((size_t)hidden);
+    if (!q) return FC_REF_NO_MEM;
+    for (int64_t t = 0; t < tokens; ++t) {
+        for (int64_t c = 0; c < gpr; ++c)
+            fc_ref_quantize_group_f32(x + t * hidden + c * group, group, bits,
+                                      q + c * group, &scales[t * gpr + c], &zeros[t * gpr + c]);
+        pack_row(q, hidden, bits, codes + t * row_bytes);
+    }
+    free(q);
+    return FC_REF_OK;
+}
+
+/* Algorithm 1, first FinegrainedQuantize: the input is binary16 and is widened
+   exactly to fp32 before Eq. 1-2. */
+int fc_ref_quantize(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                    uint8_t *codes, float *scales, float *zeros)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x_f16 || !codes || !scales || !zeros) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    float *xf = (float *)malloc(sizeof(float) * (size_t)hidden);
+    uint8_t *q = (uint8_t *)malloc((size_t)hidden);
+    if (!xf || !q) { free(xf); free(q); return FC_REF_NO_MEM; }
+    for (int64_t t = 0; t < tokens; ++t) {
+        for (int64_t h = 0; h < hidden; ++h) xf[h] = fc_ref_half_to_float(x_f16[t * hidden + h]);
+        for (int64_t c = 0; c < gpr; ++c)
+            fc_ref_quantize_group_f32(xf + c * group, group, bits,
+                                      q + c * group, &scales[t * gpr + c], &zeros[t * gpr + c]);
+        pack_row(q, hidden, bits, codes + t * row_bytes);
+    }
+    free(xf);
+    free(q);
+    return FC_REF_OK;
+}
+
+/* Dequantize (R2) to fp32: x^ = (q - z) * s, one subtraction and one product. */
+int fc_ref_dequantize_f32(const uint8_t *codes, const float *scales, const float *zeros,
+                          int64_t tokens, int64_t hidden, int group, int bits, float *y)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !zeros || !y) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            const float d = (float)code_at(codes + t * row_bytes, h, bits) - zeros[gi];
+            y[t * hidden + h] = d * scales[gi];
+        }
+    return FC_REF_OK;
+}
+
+/* Algorithm 1, last Dequantize: the recovered values are binary16 (RNE). */
+int fc_ref_dequantize(const uint8_t *codes, const float *scales, const float *zeros,
+                      int64_t tokens, int64_t hidden, int group, int bits, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !zeros || !y_f16) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            const float d = (float)code_at(codes + t * row_bytes, h, bits) - zeros[gi];
+            y_f16[t * hidden + h] = fc_ref_float_to_half(d * scales[gi]);
+        }
+    return FC_REF_OK;
+}
+
+/* Algorithm 1, the Dequantize loop over the N received slices followed by
+   ReduceSum (R6, R7).  Source j's codes start at codes_in + j*codes_stride
+   bytes, its scales/zeros at +j*meta_stride floats.  acc: fp32 [tokens,hidden]. */
+int fc_ref_dequant_reduce_f32(const uint8_t *codes_in, int64_t codes_stride,
+                              const float *scales_in, const float *zeros_in, int64_t meta_stride,
+                              int n_src, int64_t tokens, int64_t hidden, int group, int bits_in,
+                              float *acc)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes_in || !scales_in || !zeros_in || !acc) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits_in / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            float a = 0.0f;
+            for (int j = 0; j < n_src; ++j) {
+                const uint8_t *row = codes_in + (int64_t)j * codes_stride + t * row_bytes;
+                const float d = (float)code_at(row, h, bits_in) - zeros_in[(int64_t)j * meta_stride + gi];
+                a = fmaf(d, scales_in[(int64_t)j * meta_stride + gi], a);
+            }
+            acc[t * hidden + h] = a;
+        }
+    return FC_REF_OK;
+}
+
+/* Algorithm 1, middle of the loop body: Dequantize x N, ReduceSum, then the
+   second FinegrainedQuantize with bits_out. */
+int fc_ref_dequant_reduce_requant(const uint8_t *codes_in, int64_t codes_stride,
+                                  const float *scales_in, const float *zeros_in, int64_t meta_stride,
+                                  int n_src, int64_t tokens, int64_t hidden, int group,
+                                  int bits_in, int bits_out,
+                                  uint8_t *codes_out, float *scales_out, float *zeros_out)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || !check_shape(tokens, hidden, group, bits_out)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    float *acc = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!acc) return FC_REF_NO_MEM;
+    int rc = fc_ref_dequant_reduce_f32(codes_in, codes_stride, scales_in, zeros_in, meta_stride,
+                                       n_src, tokens, hidden, group, bits_in, acc);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_quantize_f32(acc, tokens, hidden, group, bits_out, codes_out, scales_out, zeros_out);
+    free(acc);
+    return rc;
+}
+
+/* Algorithm 1 end to end on one device, the two exchanges being identity
+   copies: x_f16 is [n_src, tokens, hidden] (the N ranks' partial activations),
+   y_f16 is [tokens, hidden].  The volume is quantized and dequantized exactly
+   twice (Table 1, "QDQ Step"). */
+int fc_ref_allreduce_sim(const uint16_t *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                         int group, int bits_rs, int bits_ag, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits_rs) || !check_shape(tokens, hidden, group, bits_ag)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    const int64_t m = tokens * hidden, ng = m / group;
+    const int64_t cb_rs = m * bits_rs / 8, cb_ag = m * bits_ag / 8;
+    uint8_t *c1 = (uint8_t *)malloc((size_t)(cb_rs * n_src));
+    float *s1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    float *z1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    uint8_t *c2 = (uint8_t *)malloc((size_t)cb_ag);
+    float *s2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    float *z2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    int rc = (c1 && s1 && z1 && c2 && s2 && z2) ? FC_REF_OK : FC_REF_NO_MEM;
+    for (int j = 0; rc == FC_REF_OK && j < n_src; ++j)
+        rc = fc_ref_quantize(x_f16 + (int64_t)j * m, tokens, hidden, group, bits_rs,
+                             c1 + (int64_t)j * cb_rs, s1 + (int64_t)j * ng, z1 + (int64_t)j * ng);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequant_reduce_requant(c1, cb_rs, s1, z1, ng, n_src, tokens, hidden, group,
+                                           bits_rs, bits_ag, c2, s2, z2);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequantize(c2, s2, z2, tokens, hidden, group, bits_ag, y_f16);
+    free(c1); free(s1); free(z1); free(c2); free(s2); free(z2);
+    return rc;
+}
