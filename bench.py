@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the Flash Communication quantization path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over one batch of `--batch` independent
+all-reduce volumes, stage by stage: N x fc_quantize for every volume of the
+batch, then fc_dequant_reduce_requant for every volume, then fc_dequantize for
+every volume.  Running a batch stage-major means that no kernel reads data its
+producer has just left in the 256 MB memory-side cache (several gigabytes of
+other traffic lie in between), so every timed byte comes from HBM, and the
+launches of one kernel are back to back, so an event pair around a stage
+measures sustained launch-to-launch time.  `--dependent` runs the stages of one
+volume back to back instead (cache-warm hand-over, reported for comparison).
+
+Prints ONE JSON line.  `value` is the metric named in the benchmark spec: achieved
+GB/s of the fused dequant-reduce-requant kernel (algorithmic bytes per launch /
+mean launch duration, HIP events on the launch stream inside the timed region).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
+
+
+def fused_bytes(w) -> int:
+    """Algorithmic bytes of one fused launch: N x (codes + scale + zero-point) in,
+    codes + scale + zero-point out (fp32 meta, 8 bytes per group)."""
+    m = w.elements
+    return w.n_src * (m * w.bits_in // 8 + 8 * m // w.group) + m * w.bits_out // 8 + 8 * m // w.group
+
+
+def quantize_bytes(w) -> int:
+    m = w.elements
+    return 2 * m + m * w.bits_in // 8 + 8 * m // w.group
+
+
+def dequantize_bytes(w) -> int:
+    m = w.elements
+    return m * w.bits_out // 8 + 8 * m // w.group + 2 * m
+
+
+def load_traffic(name):
+    """HBM bytes per fused launch measured with rocprofv3 --pmc (committed summary)."""
+    p = os.path.join(ROOT, "profiles", "traffic_%s.json" % name)
+    if os.path.exists(p):
+        try:
+            return json.load(open(p)).get("fused_hbm_bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def cpu_baseline(w, x_host, budget_s=20.0):
+    """The oracle's fused step on the host, single thread, full volume if it fits
+    the time budget (else the leading rows)."""
+    import oracle
+    rows = w.tokens
+    est = 16e-9 * w.elements * (1 + w.n_src / 4.0) * 1.5
+    if est * 3 > budget_s:
+        rows = max(16, int(w.tokens * budget_s / (est * 3)))
+    xs = x_host[:, :rows]
+    parts = [oracle.quantize(xs[j], w.group, w.bits_in) for j in range(w.n_src)]
+    c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
+    z = np.stack([p[2] for p in parts])
+    best = None
+    for _ in range(2):
+        t0 = time.perf_counter()
+        oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    frac = rows / w.tokens
+    return {
+        "value": round(fused_bytes(w) * frac / best / 1e9, 4),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "fused step of the plain-C oracle on rows [0,%d) of %d of volume 0, best of 2, "
+                  "%.2f s per run" % (rows, w.tokens, best),
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama3_70b_prefill", choices=sorted(synth_inputs.WORKLOADS))
+    ap.add_argument("--batch", type=int, default=0,
+                    help="independent volumes per step (0 = enough for >= 4 GiB of traffic per step)")
+    ap.add_argument("--dependent", action="store_true", help="run the stages of one volume back to back")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+
+    if a.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU's share of the path only; "
+                 "--gpus %d is not supported (run with --gpus 1)" % a.gpus)
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    import paper_2412_04964_amd as fc
+    fc.lib()
+
+    w = synth_inputs.WORKLOADS[a.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, H, N, g = w.tokens, w.hidden, w.n_src, w.group
+    vol_bytes = N * quantize_bytes(w) + fused_bytes(w) + dequantize_bytes(w)
+    B = a.batch or max(4, min(256, -(-(4 << 30) // vol_bytes)))
+
+    # volumes and per-volume intermediates, all resident in HBM before timing
+    X = [synth_inputs.make_partials_device(N, T, H, w.seed + k, dev, w.outlier_frac, w.outlier_gain)
+         for k in range(B)]
+    C1 = [torch.empty((N, T, H * w.bits_in // 8), dtype=torch.uint8, device=dev) for _ in range(B)]
+    S1 = [torch.empty((N, T, H // g), dtype=torch.float32, device=dev) for _ in range(B)]
+    Z1 = [torch.empty_like(S1[0]) for _ in range(B)]
+    C2 = [torch.empty((T, H * w.bits_out // 8), dtype=torch.uint8, device=dev) for _ in range(B)]
+    S2 = [torch.empty((T, H // g), dtype=torch.float32, device=dev) for _ in range(B)]
+    Z2 = [torch.empty_like(S2[0]) for _ in range(B)]
+    Y = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in range(B)]
+
+    def stage_quantize(k):
+        for j in range(N):
+            fc.quantize(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j], Z1[k][j]))
+
+    def stage_fused(k):
+        fc.dequant_reduce_requant(C1[k], S1[k], Z1[k], H, g, w.bits_in, w.bits_out,
+                                  out=(C2[k], S2[k], Z2[k]))
+
+    def stage_dequantize(k):
+        fc.dequantize(C2[k], S2[k], Z2[k], H, g, w.bits_out, out=Y[k])
+
+    ev = {name: [] for name in ("q", "f", "d")}
+
+    def step(timed):
+        if a.dependent:
+            for k in range(B):
+                m = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+                if timed: m[0].record()
+                stage_quantize(k)
+                if timed: m[1].record()
+                stage_fused(k)
+                if timed: m[2].record()
+                stage_dequantize(k)
+                if timed:
+                    m[3].record()
+                    ev["q"].append((m[0], m[1], 1)); ev["f"].append((m[1], m[2], 1))
+                    ev["d"].append((m[2], m[3], 1))
+            return
+        m = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+        if timed: m[0].record()
+        for k in range(B):
+            stage_quantize(k)
+        if timed: m[1].record()
+        for k in range(B):
+            stage_fused(k)
+        if timed: m[2].record()
+        for k in range(B):
+            stage_dequantize(k)
+        if timed:
+            m[3].record()
+            ev["q"].append((m[0], m[1], B)); ev["f"].append((m[1], m[2], B)); ev["d"].append((m[2], m[3], B))
+
+    for _ in range(max(1, a.warmup)):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # mean milliseconds per volume of each stage
+    ms = {k: float(sum(s.elapsed_time(e) for s, e, _ in v) / sum(n for _, _, n in v)) for k, v in ev.items()}
+    fused_s = ms["f"] * 1e-3
+    fb = fused_bytes(w)
+    achieved = fb / fused_s / 1e9
+
+    out = {
+        "metric": "fused dequant-reduce-requant GB/s on 1 MI355X",
+        "value": round(achieved, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(wall / a.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: N=%d partial fp16 tensors of %d tokens x %d hidden, N(0,1) with %g%% outlier "
+                        "channels x%g, INT%d->INT%d asymmetric, group %d"
+                        % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain, w.bits_in, w.bits_out, g),
+            "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
+            "volumes_per_step": B,
+            "stage_order": "volume-major (dependent)" if a.dependent else "stage-major over the batch",
+        },
+        "pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
+        "stages": {
+            "quantize_xN": {"us": round(ms["q"] * 1e3, 2),
+                            "GBps": round(N * quantize_bytes(w) / (ms["q"] * 1e-3) / 1e9, 1)},
+            "dequant_reduce_requant": {"us": round(ms["f"] * 1e3, 2), "GBps": round(achieved, 1)},
+            "dequantize": {"us": round(ms["d"] * 1e3, 2),
+                           "GBps": round(dequantize_bytes(w) / (ms["d"] * 1e-3) / 1e9, 1)},
+            "whole_path_GBps": round(B * vol_bytes / (wall / a.steps) / 1e9, 1),
+        },
+        "roofline": {
+            "kernel": "k_dequant_reduce_requant<%d,%d,%d>" % (w.bits_in, w.bits_out, N),
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "algorithmic_bytes_per_launch": fb,
+            "us_per_launch": round(ms["f"] * 1e3, 2),
+            "launches_timed": a.steps * B,
+            "traffic": load_traffic(w.name),
+        },
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, X[0].cpu().numpy())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

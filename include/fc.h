@@ -1,0 +1,150 @@
+/*
+ * fc.h -- C ABI of the MI355X (gfx950) Flash Communication quantization path.
+ *
+ * The library implements, on ONE GPU, the arithmetic that Flash Communication
+ * (arXiv 2412.04964) wraps around its two exchanges (Algorithm 1, Section 3.2.2):
+ *
+ *     FinegrainedQuantize  ->  [All2All]  ->  Dequantize x N, ReduceSum,
+ *     FinegrainedQuantize  ->  [All-Gather]  ->  Dequantize
+ *
+ * The exchanges themselves are not part of this library: the N partial tensors
+ * (or their quantized slices) are simply N slabs in this GPU's memory.
+ *
+ * Quantizer (Appendix "Quantization Fundamentals", Eq. 1-2, asymmetric; groups
+ * of `group` consecutive elements along `hidden`, Section 3.2.1), in fp32 with
+ * round-to-nearest-even, evaluated exactly in this order for every group:
+ *     mn, mx   = min, max of the group
+ *     s        = (mx - mn) / (2^bits - 1)          one IEEE divide
+ *     if !(s >= FLT_MIN):  s = |mn| >= FLT_MIN ? |mn| : 1       (constant group)
+ *     inv      = 1 / s                              one IEEE divide
+ *     z        = 0 - rint(mn * inv)                 integer-valued, NOT clamped
+ *     q        = clamp(rint(x * inv) + z, 0, 2^bits - 1)
+ * Dequantize (the inverse of Eq. 2):   x^ = (q - z) * s      (fp32 sub, fp32 mul)
+ * ReduceSum: acc = +0; for j = 0..N-1 in order: acc = fma(q_j - z_j, s_j, acc).
+ *
+ * Data layouts (all device memory, dense, row-major):
+ *   x, y     IEEE binary16 [tokens, hidden]
+ *   codes    bytes [tokens, hidden*bits/8].  8 bit: one code per byte.  4 bit:
+ *            two codes per byte, element 2k in bits 0-3, element 2k+1 in bits 4-7.
+ *   scales   float [tokens, hidden/group]
+ *   zeros    float [tokens, hidden/group]   (the zero-points z above)
+ *
+ * Common rules for every entry point
+ *   - All pointers are DEVICE pointers unless stated otherwise, owned by the
+ *     caller, 16-byte aligned (base pointers; the per-source meta slabs at
+ *     +j*meta_src_stride_elems only need float alignment).  Inputs are never written; outputs must not
+ *     overlap inputs.  The library allocates nothing and keeps no state except
+ *     the last HIP error code.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronizes.  The device that is current
+ *     on the calling thread must own the buffers and the stream.
+ *   - bits in {4, 8};  group in {32, 64, 128, 256, 512, 1024, 2048};
+ *     hidden % group == 0;  tokens >= 0 (0 is a no-op returning FC_OK);
+ *     tokens*hidden <= 2^36;  1 <= n_src <= FC_MAX_SRC.
+ *   - Inputs must be finite.  NaN / Inf inputs give unspecified codes.
+ *   - Return value: FC_OK or a negative FC_ERR_* code.  Argument checks come
+ *     first and make no HIP call, so they work on a host without a GPU.
+ */
+#ifndef FC_H
+#define FC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define FC_API __attribute__((visibility("default")))
+#else
+#define FC_API
+#endif
+
+#define FC_MAX_SRC 8
+
+enum {
+    FC_OK = 0,
+    FC_ERR_NULL = -1,       /* a required pointer is NULL */
+    FC_ERR_BITS = -2,       /* bit-width not 4 or 8 */
+    FC_ERR_GROUP = -3,      /* unsupported group size, or hidden % group != 0 */
+    FC_ERR_SHAPE = -4,      /* tokens < 0, hidden <= 0, too many elements, n_src out of range,
+                               or a source stride smaller than one slab */
+    FC_ERR_ALIGN = -5,      /* pointer or stride not 16-byte aligned */
+    FC_ERR_WORKSPACE = -6,  /* workspace NULL or too small */
+    FC_ERR_HIP = -7         /* kernel launch failed; see fc_last_hip_error() */
+};
+
+/*
+ * FinegrainedQuantize of Algorithm 1 (first call), Eq. 1-2.
+ *   x_f16   in   binary16 [tokens, hidden]
+ *   codes   out  [tokens, hidden*bits/8] bytes
+ *   scales  out  float [tokens, hidden/group]
+ *   zeros   out  float [tokens, hidden/group]
+ */
+FC_API int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                void *codes, float *scales, float *zeros, void *hip_stream);
+
+/*
+ * The body of Algorithm 1 between the two exchanges, fused: Dequantize each of
+ * the n_src received slices with its own scale and zero-point, ReduceSum (fp32
+ * FMA chain, source order), FinegrainedQuantize of the sum with bits_out.  The
+ * fp32 sum never goes to memory.  bits_in = 4 with bits_out = 8 is the paper's
+ * "INT6" setting (Section 3.2.3).
+ *   codes_in   in  source j's codes start at (char*)codes_in + j*codes_src_stride_bytes,
+ *                  each [tokens, hidden*bits_in/8]
+ *   scales_in, zeros_in
+ *              in  source j's arrays start at +j*meta_src_stride_elems floats,
+ *                  each [tokens, hidden/group]
+ *   codes_src_stride_bytes >= tokens*hidden*bits_in/8, multiple of 16;
+ *   meta_src_stride_elems  >= tokens*hidden/group (both ignored when
+ *   n_src == 1).
+ *   codes_out, scales_out, zeros_out   out, as in fc_quantize with bits_out.
+ */
+FC_API int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
+                              const float *scales_in, const float *zeros_in,
+                              int64_t meta_src_stride_elems,
+                              int n_src, int64_t tokens, int64_t hidden, int group,
+                              int bits_in, int bits_out,
+                              void *codes_out, float *scales_out, float *zeros_out,
+                              void *hip_stream);
+
+/*
+ * Dequantize of Algorithm 1 (last call): y = binary16_rne((q - z) * s).
+ * Values beyond the binary16 range become infinities.
+ */
+FC_API int fc_dequantize(const void *codes, const float *scales, const float *zeros,
+                  int64_t tokens, int64_t hidden, int group, int bits,
+                  void *y_f16, void *hip_stream);
+
+/*
+ * Algorithm 1 end to end on one device with identity exchanges:
+ * n_src x fc_quantize(bits_rs) into the workspace, fc_dequant_reduce_requant
+ * (bits_rs -> bits_ag), fc_dequantize.  The volume is quantized and dequantized
+ * exactly twice (Table 1, "QDQ Step").
+ *   x_f16      in   binary16 [n_src, tokens, hidden]
+ *   y_f16      out  binary16 [tokens, hidden]
+ *   workspace  device scratch of at least fc_allreduce_sim_workspace_bytes(...)
+ *              bytes, 16-byte aligned; contents on return are unspecified.
+ */
+FC_API int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                     int group, int bits_rs, int bits_ag, void *y_f16,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes fc_allreduce_sim needs; 0 if the arguments are invalid. */
+FC_API size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
+                                        int bits_rs, int bits_ag);
+
+/* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
+FC_API const char *fc_strerror(int code);
+
+/* Raw hipError_t of the most recent failed launch on this thread (0 if none). */
+FC_API int fc_last_hip_error(void);
+
+/* major*10000 + minor*100 + patch */
+FC_API int fc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FC_H */

@@ -1,0 +1,26 @@
+"""MI355X-native Flash Communication quantization path (arXiv 2412.04964).
+
+Thin ctypes binding over ``libfc.so`` (the C ABI in ``include/fc.h``).  The
+functions here only marshal arguments: they take torch CUDA tensors for device
+memory, pass raw pointers and the current HIP stream, and raise on any error
+code.  There is no CPU fallback: if the HIP library is missing or no GPU is
+present the compute calls fail loudly.
+"""
+from .binding import (  # noqa: F401
+    FcError,
+    allreduce_sim,
+    allreduce_sim_workspace_bytes,
+    dequant_reduce_requant,
+    dequantize,
+    last_hip_error,
+    lib,
+    lib_path,
+    quantize,
+    strerror,
+    version,
+)
+
+__all__ = [
+    "FcError", "allreduce_sim", "allreduce_sim_workspace_bytes", "dequant_reduce_requant",
+    "dequantize", "last_hip_error", "lib", "lib_path", "quantize", "strerror", "version",
+]

@@ -1,0 +1,221 @@
+// fc_api.hip -- the extern "C" boundary declared in include/fc.h: argument
+// checks (no HIP call before they pass), shape bookkeeping and kernel dispatch.
+#include "fc.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fc_launch.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr int64_t kMaxElems = (int64_t)1 << 36;   // keeps grid*block below 2^32 threads
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int log2_exact(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return ((1 << s) == v) ? s : -1;
+}
+
+// Checks common to every entry point.  On success *n_elems = tokens*hidden.
+int check_shape(int64_t tokens, int64_t hidden, int group, int bits, int64_t *n_elems)
+{
+    if (bits != 4 && bits != 8) return FC_ERR_BITS;
+    const int sh = log2_exact(group);
+    if (sh < 5 || sh > 11) return FC_ERR_GROUP;            // 32 .. 2048
+    if (tokens < 0 || hidden <= 0) return FC_ERR_SHAPE;
+    if (hidden % group != 0) return FC_ERR_GROUP;
+    if (hidden > kMaxElems || (tokens > 0 && tokens > kMaxElems / hidden)) return FC_ERR_SHAPE;
+    *n_elems = tokens * hidden;
+    return FC_OK;
+}
+
+int hip_result(hipError_t e)
+{
+    if (e == hipSuccess) return FC_OK;
+    g_last_hip_error = (int)e;
+    return FC_ERR_HIP;
+}
+
+struct SimLayout {
+    size_t codes_rs;     // bytes of one source's codes
+    size_t meta;         // bytes of one scales (or zeros) array
+    size_t off_codes1, off_scales1, off_zeros1, off_codes2, off_scales2, off_zeros2, total;
+};
+
+size_t round16(size_t v) { return (v + 15u) & ~(size_t)15u; }
+
+SimLayout sim_layout(int n_src, int64_t n_elems, int group, int bits_rs, int bits_ag)
+{
+    SimLayout L;
+    L.codes_rs = round16((size_t)(n_elems * bits_rs / 8));
+    L.meta = round16((size_t)(n_elems / group) * sizeof(float));
+    const size_t codes_ag = round16((size_t)(n_elems * bits_ag / 8));
+    size_t off = 0;
+    L.off_codes1 = off;  off += L.codes_rs * n_src;
+    L.off_scales1 = off; off += L.meta * n_src;
+    L.off_zeros1 = off;  off += L.meta * n_src;
+    L.off_codes2 = off;  off += codes_ag;
+    L.off_scales2 = off; off += L.meta;
+    L.off_zeros2 = off;  off += L.meta;
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                void *codes, float *scales, float *zeros, void *hip_stream)
+{
+    int64_t n = 0;
+    const int rc = check_shape(tokens, hidden, group, bits, &n);
+    if (rc != FC_OK) return rc;
+    if (n == 0) return FC_OK;
+    if (!x_f16 || !codes || !scales || !zeros) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros))
+        return FC_ERR_ALIGN;
+    return hip_result(fc::launch_quantize(bits, x_f16, n, group / 32, log2_exact(group), codes,
+                                          scales, zeros, static_cast<hipStream_t>(hip_stream)));
+}
+
+int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
+                              const float *scales_in, const float *zeros_in,
+                              int64_t meta_src_stride_elems,
+                              int n_src, int64_t tokens, int64_t hidden, int group,
+                              int bits_in, int bits_out,
+                              void *codes_out, float *scales_out, float *zeros_out,
+                              void *hip_stream)
+{
+    int64_t n = 0;
+    int rc = check_shape(tokens, hidden, group, bits_in, &n);
+    if (rc != FC_OK) return rc;
+    if (bits_out != 4 && bits_out != 8) return FC_ERR_BITS;
+    if (n_src < 1 || n_src > FC_MAX_SRC) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!codes_in || !scales_in || !zeros_in || !codes_out || !scales_out || !zeros_out)
+        return FC_ERR_NULL;
+    if (n_src > 1) {
+        if (codes_src_stride_bytes < n * bits_in / 8 || meta_src_stride_elems < n / group)
+            return FC_ERR_SHAPE;
+        if ((codes_src_stride_bytes & 15) != 0) return FC_ERR_ALIGN;
+    } else {
+        codes_src_stride_bytes = 0;
+        meta_src_stride_elems = 0;
+    }
+    if (!aligned16(codes_in) || !aligned16(scales_in) || !aligned16(zeros_in) ||
+        !aligned16(codes_out) || !aligned16(scales_out) || !aligned16(zeros_out))
+        return FC_ERR_ALIGN;
+
+    fc::FusedArgs a;
+    a.codes_in = codes_in;
+    a.codes_stride = codes_src_stride_bytes;
+    a.scales_in = scales_in;
+    a.zeros_in = zeros_in;
+    a.meta_stride = meta_src_stride_elems;
+    a.n_src = n_src;
+    a.n_elems = n;
+    a.lpg = group / 32;
+    a.group_shift = log2_exact(group);
+    a.codes_out = codes_out;
+    a.scales_out = scales_out;
+    a.zeros_out = zeros_out;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (bits_in == 4)
+        e = (bits_out == 4) ? fc::launch_fused_4_4(a, st) : fc::launch_fused_4_8(a, st);
+    else
+        e = (bits_out == 4) ? fc::launch_fused_8_4(a, st) : fc::launch_fused_8_8(a, st);
+    return hip_result(e);
+}
+
+int fc_dequantize(const void *codes, const float *scales, const float *zeros,
+                  int64_t tokens, int64_t hidden, int group, int bits,
+                  void *y_f16, void *hip_stream)
+{
+    int64_t n = 0;
+    const int rc = check_shape(tokens, hidden, group, bits, &n);
+    if (rc != FC_OK) return rc;
+    if (n == 0) return FC_OK;
+    if (!codes || !scales || !zeros || !y_f16) return FC_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(zeros) || !aligned16(y_f16))
+        return FC_ERR_ALIGN;
+    return hip_result(fc::launch_dequantize(bits, codes, scales, zeros, n, log2_exact(group), y_f16,
+                                            static_cast<hipStream_t>(hip_stream)));
+}
+
+size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
+                                        int bits_rs, int bits_ag)
+{
+    int64_t n = 0;
+    if (check_shape(tokens, hidden, group, bits_rs, &n) != FC_OK) return 0;
+    if (bits_ag != 4 && bits_ag != 8) return 0;
+    if (n_src < 1 || n_src > FC_MAX_SRC) return 0;
+    return sim_layout(n_src, n, group, bits_rs, bits_ag).total;
+}
+
+int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                     int group, int bits_rs, int bits_ag, void *y_f16,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int64_t n = 0;
+    const int rc = check_shape(tokens, hidden, group, bits_rs, &n);
+    if (rc != FC_OK) return rc;
+    if (bits_ag != 4 && bits_ag != 8) return FC_ERR_BITS;
+    if (n_src < 1 || n_src > FC_MAX_SRC) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!x_f16 || !y_f16) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return FC_ERR_ALIGN;
+    const SimLayout L = sim_layout(n_src, n, group, bits_rs, bits_ag);
+    if (!workspace || workspace_bytes < L.total) return FC_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FC_ERR_ALIGN;
+
+    char *ws = static_cast<char *>(workspace);
+    const char *x = static_cast<const char *>(x_f16);
+    for (int j = 0; j < n_src; ++j) {
+        const int q = fc_quantize(x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
+                                  ws + L.off_codes1 + (size_t)j * L.codes_rs,
+                                  reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
+                                  reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta),
+                                  hip_stream);
+        if (q != FC_OK) return q;
+    }
+    const int f = fc_dequant_reduce_requant(
+        ws + L.off_codes1, (int64_t)L.codes_rs,
+        reinterpret_cast<const float *>(ws + L.off_scales1),
+        reinterpret_cast<const float *>(ws + L.off_zeros1), (int64_t)(L.meta / sizeof(float)),
+        n_src, tokens, hidden, group, bits_rs, bits_ag, ws + L.off_codes2,
+        reinterpret_cast<float *>(ws + L.off_scales2), reinterpret_cast<float *>(ws + L.off_zeros2),
+        hip_stream);
+    if (f != FC_OK) return f;
+    return fc_dequantize(ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
+                         reinterpret_cast<const float *>(ws + L.off_zeros2), tokens, hidden, group,
+                         bits_ag, y_f16, hip_stream);
+}
+
+const char *fc_strerror(int code)
+{
+    switch (code) {
+    case FC_OK: return "success";
+    case FC_ERR_NULL: return "a required pointer is NULL";
+    case FC_ERR_BITS: return "bit-width must be 4 or 8";
+    case FC_ERR_GROUP: return "group must be a power of two in [32, 2048] that divides hidden";
+    case FC_ERR_SHAPE: return "bad tokens / hidden / n_src / source stride";
+    case FC_ERR_ALIGN: return "pointers and strides must be 16-byte aligned";
+    case FC_ERR_WORKSPACE: return "workspace missing or too small";
+    case FC_ERR_HIP: return "HIP launch failed (see fc_last_hip_error)";
+    default: return "unknown error code";
+    }
+}
+
+int fc_last_hip_error(void) { return g_last_hip_error; }
+
+int fc_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// fc_codec.hip -- launchers of the stand-alone quantize and dequantize kernels.
+#include "fc_device.hpp"
+#include "fc_launch.hpp"
+
+namespace fc {
+
+hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int lpg, int group_shift,
+                           void *codes, float *scales, float *zeros, hipStream_t stream)
+{
+    const int64_t blocks = (n_elems + kBlockElems - 1) / kBlockElems;
+    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    const uint16_t *x = static_cast<const uint16_t *>(x_f16);
+    uint8_t *c = static_cast<uint8_t *>(codes);
+    if (bits == 4)
+        k_quantize<4><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, zeros);
+    else
+        k_quantize<8><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, zeros);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(int bits, const void *codes, const float *scales, const float *zeros,
+                             int64_t n_elems, int group_shift, void *y_f16, hipStream_t stream)
+{
+    const int64_t blocks = (n_elems + kBlockElems - 1) / kBlockElems;
+    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    const uint8_t *c = static_cast<const uint8_t *>(codes);
+    uint16_t *y = static_cast<uint16_t *>(y_f16);
+    if (bits == 4)
+        k_dequantize<4><<<grid, block, 0, stream>>>(c, scales, zeros, n_elems, group_shift, y);
+    else
+        k_dequantize<8><<<grid, block, 0, stream>>>(c, scales, zeros, n_elems, group_shift, y);
+    return hipGetLastError();
+}
+
+}  // namespace fc

@@ -1,0 +1,43 @@
+// fc_fused.hip -- instantiations of the fused Dequantize-ReduceSum-Quantize
+// kernel for one (FC_BITS_IN, FC_BITS_OUT) pair and every fan-in 1..8.
+// Compiled once per pair (the build defines the two macros).
+#include "fc_device.hpp"
+#include "fc_launch.hpp"
+
+#if !defined(FC_BITS_IN) || !defined(FC_BITS_OUT)
+#error "define FC_BITS_IN and FC_BITS_OUT (4 or 8)"
+#endif
+
+#define FC_CAT3(a, b, c) a##b##_##c
+#define FC_NAME(in, out) FC_CAT3(launch_fused_, in, out)
+
+namespace fc {
+
+template <int NSRC>
+static hipError_t launch_n(const FusedArgs &a, hipStream_t stream)
+{
+    const int64_t blocks = (a.n_elems + kBlockElems - 1) / kBlockElems;
+    k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC>
+        <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+            static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
+            a.meta_stride, a.n_elems, a.lpg, a.group_shift, static_cast<uint8_t *>(a.codes_out),
+            a.scales_out, a.zeros_out);
+    return hipGetLastError();
+}
+
+hipError_t FC_NAME(FC_BITS_IN, FC_BITS_OUT)(const FusedArgs &a, hipStream_t stream)
+{
+    switch (a.n_src) {
+    case 1: return launch_n<1>(a, stream);
+    case 2: return launch_n<2>(a, stream);
+    case 3: return launch_n<3>(a, stream);
+    case 4: return launch_n<4>(a, stream);
+    case 5: return launch_n<5>(a, stream);
+    case 6: return launch_n<6>(a, stream);
+    case 7: return launch_n<7>(a, stream);
+    case 8: return launch_n<8>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fc

@@ -1,0 +1,39 @@
+// fc_launch.hpp -- host-side launch functions implemented by the .hip units.
+// Internal to the library; the public interface is include/fc.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fc {
+
+// n_elems = tokens*hidden (a multiple of the group size); lpg = group/32 lanes
+// per group; group_shift = log2(group).  All pointers are device pointers.
+hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int lpg, int group_shift,
+                           void *codes, float *scales, float *zeros, hipStream_t stream);
+
+hipError_t launch_dequantize(int bits, const void *codes, const float *scales, const float *zeros,
+                             int64_t n_elems, int group_shift, void *y_f16, hipStream_t stream);
+
+struct FusedArgs {
+    const void *codes_in;
+    int64_t codes_stride;
+    const float *scales_in;
+    const float *zeros_in;
+    int64_t meta_stride;
+    int n_src;
+    int64_t n_elems;
+    int lpg;
+    int group_shift;
+    void *codes_out;
+    float *scales_out;
+    float *zeros_out;
+};
+
+// one translation unit per (bits_in, bits_out) pair
+hipError_t launch_fused_4_4(const FusedArgs &a, hipStream_t stream);
+hipError_t launch_fused_4_8(const FusedArgs &a, hipStream_t stream);
+hipError_t launch_fused_8_4(const FusedArgs &a, hipStream_t stream);
+hipError_t launch_fused_8_8(const FusedArgs &a, hipStream_t stream);
+
+}  // namespace fc

@@ -1,0 +1,116 @@
+"""Host-only checks of the C-ABI library: it loads, exports every function that
+include/fc.h declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2412_04964_amd as fc
+    if not os.path.exists(fc.lib_path()):
+        from paper_2412_04964_amd.build import build
+        build()
+    return fc.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert {"fc_quantize", "fc_dequant_reduce_requant", "fc_dequantize", "fc_allreduce_sim",
+            "fc_allreduce_sim_workspace_bytes", "fc_strerror", "fc_last_hip_error",
+            "fc_version"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_no_internal_symbols_leak(L):
+    import subprocess
+    import paper_2412_04964_amd as fc
+    out = subprocess.run(["nm", "-D", "--defined-only", fc.lib_path()], capture_output=True, text=True).stdout
+    exported = [l.split()[-1] for l in out.splitlines() if " T " in l]
+    assert sorted(exported) == declared_functions()
+
+
+P = 0x10000      # a fake, 16-byte aligned, non-NULL device address; never dereferenced
+
+
+def test_quantize_argument_checks(L):
+    q = L.fc_quantize
+    assert q(P, 4, 256, 128, 5, P, P, P, None) == -2          # bits
+    assert q(P, 4, 256, 100, 8, P, P, P, None) == -3          # group not a power of two
+    assert q(P, 4, 256, 16, 8, P, P, P, None) == -3           # group too small
+    assert q(P, 4, 256, 4096, 8, P, P, P, None) == -3         # group too large
+    assert q(P, 4, 192, 128, 8, P, P, P, None) == -3          # hidden % group
+    assert q(P, -1, 256, 128, 8, P, P, P, None) == -4         # tokens
+    assert q(P, 4, 0, 128, 8, P, P, P, None) == -4            # hidden
+    assert q(P, 1 << 40, 1 << 20, 128, 8, P, P, P, None) == -4  # too many elements
+    assert q(None, 4, 256, 128, 8, P, P, P, None) == -1
+    assert q(P, 4, 256, 128, 8, P, None, P, None) == -1
+    assert q(P + 8, 4, 256, 128, 8, P, P, P, None) == -5
+    assert q(P, 4, 256, 128, 8, P, P, P + 4, None) == -5
+    assert q(None, 0, 256, 128, 8, None, None, None, None) == 0   # empty input is a no-op
+
+
+def test_fused_argument_checks(L):
+    f = L.fc_dequant_reduce_requant
+    ok = dict(tokens=4, hidden=256, group=128)
+    cs, ms = 4 * 256 // 2, 8      # 4-bit slab bytes, groups per slab
+
+    def call(codes=P, cstride=cs, sc=P, ze=P, mstride=ms, n=4, bits_in=4, bits_out=4, co=P, so=P, zo=P,
+             **kw):
+        a = dict(ok); a.update(kw)
+        return f(codes, cstride, sc, ze, mstride, n, a["tokens"], a["hidden"], a["group"], bits_in,
+                 bits_out, co, so, zo, None)
+
+    assert call(bits_in=3) == -2 and call(bits_out=16) == -2
+    assert call(n=0) == -4 and call(n=9) == -4
+    assert call(cstride=cs - 16) == -4                        # slabs would overlap
+    assert call(mstride=4) == -4
+    assert call(cstride=cs + 8) == -5
+    assert call(codes=None) == -1 and call(zo=None) == -1
+    assert call(sc=P + 4) == -5
+    assert call(group=64, hidden=96) == -3
+    assert call(tokens=0, codes=None, sc=None, ze=None, co=None, so=None, zo=None) == 0
+
+
+def test_dequantize_and_sim_argument_checks(L):
+    d = L.fc_dequantize
+    assert d(P, P, P, 4, 256, 128, 7, P, None) == -2
+    assert d(P, P, P, 4, 256, 128, 8, None, None) == -1
+    assert d(P, P, P, 4, 256, 128, 8, P + 2, None) == -5
+    w = L.fc_allreduce_sim_workspace_bytes
+    assert w(4, 4, 256, 128, 3, 4) == 0 and w(0, 4, 256, 128, 4, 4) == 0
+    need = w(4, 16, 4096, 128, 4, 8)
+    m = 16 * 4096
+    assert need >= 4 * (m // 2 + 2 * 4 * m // 128) + m + 2 * 4 * m // 128
+    s = L.fc_allreduce_sim
+    assert s(P, 4, 16, 4096, 128, 4, 8, P, P, need - 1, None) == -6
+    assert s(P, 4, 16, 4096, 128, 4, 8, P, None, need, None) == -6
+    assert s(P, 4, 16, 4096, 128, 4, 9, P, P, need, None) == -2
+    assert s(P, 9, 16, 4096, 128, 4, 8, P, P, need, None) == -4
+    assert s(None, 4, 16, 4096, 128, 4, 8, P, P, need, None) == -1
+
+
+def test_strerror_and_version(L):
+    assert L.fc_version() >= 100
+    for code in range(-8, 1):
+        msg = L.fc_strerror(code)
+        assert isinstance(msg, bytes) and len(msg) > 0
+    assert L.fc_last_hip_error() == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    torch = pytest.importorskip("torch")
+    import paper_2412_04964_amd as fc
+    with pytest.raises(TypeError):
+        fc.quantize(torch.zeros(4, 256, dtype=torch.float16), 128, 8)

@@ -1,0 +1,344 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle on
+the same seeded inputs.  Codes, scales and zero-points must match bit for bit;
+the final float16 output is additionally checked against the benchmark
+contract's tolerance (1e-3 relative) although bit equality is what is expected
+and asserted.  Run with ``-m gpu`` on an MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+GUARD = 256       # bytes of poison on each side of every output buffer
+POISON = 0xA5
+
+
+@pytest.fixture(scope="module")
+def fc():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests selected but no GPU is visible")
+    import paper_2412_04964_amd as m
+    m.lib()            # raises if libfc.so was not built: there is no fallback
+    return m
+
+
+class Guarded:
+    """Device buffer with poisoned guard bands; .t is the usable tensor."""
+
+    def __init__(self, shape, dtype):
+        n = int(np.prod(shape)) * torch.empty(0, dtype=dtype).element_size()
+        pad = (-n) % 16
+        self.raw = torch.full((GUARD + n + pad + GUARD,), POISON, dtype=torch.uint8, device="cuda")
+        self.n = n
+        self.t = self.raw[GUARD:GUARD + n].view(dtype).view(*shape)
+
+    def check(self):
+        raw = self.raw.cpu().numpy()
+        assert (raw[:GUARD] == POISON).all(), "write before the buffer"
+        assert (raw[GUARD + self.n:] == POISON).all(), "write past the buffer"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def same_bits(a, b):
+    a = np.ascontiguousarray(a); b = np.ascontiguousarray(b)
+    return a.shape == b.shape and a.tobytes() == b.tobytes()
+
+
+def first_diff(a, b):
+    a = np.ascontiguousarray(a).ravel(); b = np.ascontiguousarray(b).ravel()
+    ia = a.view(np.uint32) if a.dtype == np.float32 else a
+    ib = b.view(np.uint32) if b.dtype == np.float32 else b
+    idx = np.flatnonzero(ia != ib)
+    return "%d mismatches, first at %s: gpu=%r ref=%r" % (idx.size, idx[:5], a[idx[:5]], b[idx[:5]])
+
+
+def gpu_quantize(fc, x16, group, bits):
+    t, h = x16.shape
+    c = Guarded((t, h * bits // 8), torch.uint8)
+    s = Guarded((t, h // group), torch.float32)
+    z = Guarded((t, h // group), torch.float32)
+    fc.quantize(dev(x16.view(np.uint16)).view(torch.float16), group, bits, out=(c.t, s.t, z.t))
+    torch.cuda.synchronize()
+    for g in (c, s, z):
+        g.check()
+    return c.t.cpu().numpy(), s.t.cpu().numpy(), z.t.cpu().numpy()
+
+
+def gpu_fused(fc, c, s, z, hidden, group, bits_in, bits_out):
+    t = c.shape[1]
+    co = Guarded((t, hidden * bits_out // 8), torch.uint8)
+    so = Guarded((t, hidden // group), torch.float32)
+    zo = Guarded((t, hidden // group), torch.float32)
+    fc.dequant_reduce_requant(dev(c), dev(s), dev(z), hidden, group, bits_in, bits_out,
+                              out=(co.t, so.t, zo.t))
+    torch.cuda.synchronize()
+    for g in (co, so, zo):
+        g.check()
+    return co.t.cpu().numpy(), so.t.cpu().numpy(), zo.t.cpu().numpy()
+
+
+def gpu_dequantize(fc, c, s, z, hidden, group, bits):
+    y = Guarded((c.shape[0], hidden), torch.float16)
+    fc.dequantize(dev(c), dev(s), dev(z), hidden, group, bits, out=y.t)
+    torch.cuda.synchronize()
+    y.check()
+    return y.t.cpu().numpy()
+
+
+def assert_triplet(got, want, what):
+    for name, g, w in zip(("codes", "scales", "zeros"), got, want):
+        assert same_bits(g, w), "%s %s: %s" % (what, name, first_diff(g, w))
+
+
+def assert_f16(got, want, scale_per_elem, what):
+    # contract tolerance first (1e-3 relative, floored by the group's step), then exact bits
+    g = got.astype(np.float64); w = want.astype(np.float64)
+    tol = 1e-3 * np.maximum(np.abs(w), scale_per_elem)
+    fin = np.isfinite(w)
+    assert np.all(np.abs(g - w)[fin] <= tol[fin]), what
+    assert same_bits(got.view(np.uint16), want.view(np.uint16)), \
+        "%s: %s" % (what, first_diff(got.view(np.uint16), want.view(np.uint16)))
+
+
+# shapes: several workgroup tiles (8192 elements each) plus a ragged tail
+SHAPES = [(16, 4096), (3, 1056), (5, 8192), (1, 32), (7, 2080), (33, 4096 + 2048)]
+
+
+def groups_for(hidden):
+    return [g for g in (32, 64, 128, 256, 512, 1024, 2048) if hidden % g == 0]
+
+
+# --------------------------------------------------------------------------- #
+# fc_quantize
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_quantize_matches_oracle(fc, bits, shape):
+    t, h = shape
+    x = synth_inputs.make_partials(1, t, h, seed=t + h, outlier_frac=0.01)[0]
+    for group in groups_for(h):
+        assert_triplet(gpu_quantize(fc, x, group, bits), oracle.quantize(x, group, bits),
+                       "quantize %s g=%d b=%d" % (shape, group, bits))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("group", [32, 64, 128, 256])
+def test_quantize_adversarial_groups(fc, bits, group):
+    x = synth_inputs.adversarial_groups(group, seed=group)
+    assert_triplet(gpu_quantize(fc, x, group, bits), oracle.quantize(x, group, bits),
+                   "adversarial g=%d b=%d" % (group, bits))
+
+
+def test_quantize_tiny_config_seed0(fc):
+    w = synth_inputs.WORKLOADS["tiny"]
+    x = synth_inputs.make_workload(w)
+    for j in range(w.n_src):
+        assert_triplet(gpu_quantize(fc, x[j], w.group, w.bits_in), oracle.quantize(x[j], w.group, w.bits_in),
+                       "tiny source %d" % j)
+
+
+# --------------------------------------------------------------------------- #
+# fc_dequant_reduce_requant
+# --------------------------------------------------------------------------- #
+
+def oracle_stage1(x, group, bits):
+    parts = [oracle.quantize(x[j], group, bits) for j in range(x.shape[0])]
+    return tuple(np.stack([p[i] for p in parts]) for i in range(3))
+
+
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_fused_matches_oracle(fc, bits_in, bits_out, n_src):
+    for (t, h) in [(16, 4096), (3, 1056), (7, 2080)]:
+        x = synth_inputs.make_partials(n_src, t, h, seed=10 * n_src + bits_in)
+        for group in groups_for(h)[:4]:
+            c, s, z = oracle_stage1(x, group, bits_in)
+            want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+            got = gpu_fused(fc, c, s, z, h, group, bits_in, bits_out)
+            assert_triplet(got, want, "fused N=%d %dx%d g=%d %d->%d" % (n_src, t, h, group, bits_in, bits_out))
+
+
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8)])
+def test_fused_large_groups(fc, bits_in, bits_out):
+    t, h = 5, 8192
+    x = synth_inputs.make_partials(3, t, h, seed=77)
+    for group in (512, 1024, 2048):
+        c, s, z = oracle_stage1(x, group, bits_in)
+        want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+        assert_triplet(gpu_fused(fc, c, s, z, h, group, bits_in, bits_out), want, "fused g=%d" % group)
+
+
+@pytest.mark.parametrize("bits_in", [4, 8])
+def test_fused_arbitrary_scales_and_zero_points(fc, bits_in):
+    # slices whose zero-points are huge, negative, fractional or mixed inside one
+    # wavefront: exercises the general (fp32) dequantize path next to the fast one
+    rng = np.random.default_rng(5)
+    n_src, t, h, group = 4, 6, 4096, 128
+    c = rng.integers(0, 256, size=(n_src, t, h * bits_in // 8), dtype=np.uint8)
+    s = np.exp(rng.uniform(-12, 8, size=(n_src, t, h // group))).astype(np.float32)
+    z = np.rint(rng.uniform(-20, 300, size=(n_src, t, h // group))).astype(np.float32)
+    z[0, :, ::3] = rng.uniform(-3e6, 3e6, size=z[0, :, ::3].shape).astype(np.float32)
+    z[1, :, 1::5] += 0.25
+    z[2, 1] = -1700.0
+    z[2, 2] = 1000.0
+    z[2, 3] = -1701.0
+    z[2, 4] = 1001.0
+    z[3, 0] = 2.0 ** 24 + 2
+    for bits_out in (4, 8):
+        want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+        assert_triplet(gpu_fused(fc, c, s, z, h, group, bits_in, bits_out), want,
+                       "arbitrary meta %d->%d" % (bits_in, bits_out))
+
+
+def test_fused_adversarial_sums(fc):
+    # sums that are constant, zero, or nearly constant on a large offset
+    group = 128
+    a = synth_inputs.adversarial_groups(group, seed=1)
+    x = np.stack([a, (-a.astype(np.float32)).astype(np.float16), a[::-1].copy()])
+    for bits in (4, 8):
+        c, s, z = oracle_stage1(x, group, bits)
+        for n in (2, 3):
+            want = oracle.dequant_reduce_requant(c[:n], s[:n], z[:n], a.shape[1], group, bits, bits)
+            assert_triplet(gpu_fused(fc, c[:n], s[:n], z[:n], a.shape[1], group, bits, bits), want,
+                           "adversarial sums b=%d n=%d" % (bits, n))
+
+
+def test_fused_source_stride_with_padding(fc):
+    # sources separated by more than one slab (stride > slab size)
+    n_src, t, h, group, bits = 3, 4, 2048, 128, 4
+    x = synth_inputs.make_partials(n_src, t, h, seed=9)
+    c, s, z = oracle_stage1(x, group, bits)
+    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits, bits)
+    cp = torch.zeros((n_src, t + 2, h // 2), dtype=torch.uint8, device="cuda")
+    sp = torch.zeros((n_src, t + 1, h // group), dtype=torch.float32, device="cuda")
+    zp = torch.zeros_like(sp)
+    cp[:, :t] = dev(c); sp[:, :t] = dev(s); zp[:, :t] = dev(z)
+    co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
+    so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
+    zo = torch.empty_like(so)
+    rc = fc.lib().fc_dequant_reduce_requant(cp.data_ptr(), cp.stride(0), sp.data_ptr(), zp.data_ptr(),
+                                            sp.stride(0), n_src, t, h, group, bits, bits,
+                                            co.data_ptr(), so.data_ptr(), zo.data_ptr(),
+                                            torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "padded stride")
+
+
+# --------------------------------------------------------------------------- #
+# fc_dequantize
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("shape", [(16, 4096), (3, 1056), (7, 2080)])
+def test_dequantize_matches_oracle(fc, bits, shape):
+    t, h = shape
+    x = synth_inputs.make_partials(1, t, h, seed=3)[0]
+    for group in groups_for(h)[:4]:
+        c, s, z = oracle.quantize(x, group, bits)
+        want = oracle.dequantize(c, s, z, h, group, bits)
+        got = gpu_dequantize(fc, c, s, z, h, group, bits)
+        assert_f16(got, want, np.repeat(s, group, axis=1), "dequantize %s g=%d b=%d" % (shape, group, bits))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_dequantize_extremes(fc, bits):
+    # adversarial groups (float16 extremes, subnormals), overflow to infinity, odd zero-points
+    group = 128
+    x = synth_inputs.adversarial_groups(group, seed=2)
+    c, s, z = oracle.quantize(x, group, bits)
+    h = x.shape[1]
+    want = oracle.dequantize(c, s, z, h, group, bits)
+    assert_f16(gpu_dequantize(fc, c, s, z, h, group, bits), want, np.repeat(s, group, axis=1), "extremes")
+    rng = np.random.default_rng(8)
+    s2 = np.exp(rng.uniform(-30, 12, size=s.shape)).astype(np.float32)
+    z2 = z.copy(); z2[:, ::2] = rng.uniform(-5e4, 5e4, size=z2[:, ::2].shape).astype(np.float32)
+    want = oracle.dequantize(c, s2, z2, h, group, bits)
+    got = gpu_dequantize(fc, c, s2, z2, h, group, bits)
+    assert same_bits(got.view(np.uint16), want.view(np.uint16)), first_diff(got.view(np.uint16), want.view(np.uint16))
+    assert np.isinf(want.astype(np.float32)).any() and (want.view(np.uint16) & 0x7C00 == 0).any()
+
+
+# --------------------------------------------------------------------------- #
+# fc_allreduce_sim
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("name", ["tiny"])
+def test_allreduce_sim_tiny_config(fc, name):
+    w = synth_inputs.WORKLOADS[name]
+    x = synth_inputs.make_workload(w)
+    want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
+    y = Guarded((w.tokens, w.hidden), torch.float16)
+    fc.allreduce_sim(dev(x.view(np.uint16)).view(torch.float16), w.group, w.bits_in, w.bits_out, out=y.t)
+    torch.cuda.synchronize(); y.check()
+    c, s, z = oracle_stage1(x, w.group, w.bits_in)
+    so = oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)[1]
+    assert_f16(y.t.cpu().numpy(), want, np.repeat(so, w.group, axis=1), "allreduce_sim tiny")
+
+
+@pytest.mark.parametrize("bits_rs,bits_ag", [(8, 8), (4, 4), (4, 8)])
+@pytest.mark.parametrize("n_src", [2, 4, 8])
+def test_allreduce_sim_matches_oracle(fc, bits_rs, bits_ag, n_src):
+    t, h, group = 9, 4096, 128
+    x = synth_inputs.make_partials(n_src, t, h, seed=n_src)
+    want = oracle.allreduce_sim(x, group, bits_rs, bits_ag)
+    got = fc.allreduce_sim(dev(x.view(np.uint16)).view(torch.float16), group, bits_rs, bits_ag)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert same_bits(got.view(np.uint16), want.view(np.uint16)), first_diff(got.view(np.uint16), want.view(np.uint16))
+
+
+def test_empty_input_is_a_noop(fc):
+    x = torch.empty((0, 4096), dtype=torch.float16, device="cuda")
+    c, s, z = fc.quantize(x, 128, 4)
+    assert c.shape == (0, 2048) and s.shape == (0, 32)
+    y = fc.allreduce_sim(torch.empty((4, 0, 4096), dtype=torch.float16, device="cuda"), 128, 4, 4)
+    assert y.shape == (0, 4096)
+    torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------------- #
+# full benchmark shapes, in the launch configuration the benchmark times:
+# the whole tensor goes through the GPU, sampled token rows are checked
+# against the oracle (groups never cross rows, so a row is self-contained)
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("name", ["llama3_8b_prefill", "llama3_70b_prefill", "wide_fanin", "decode"])
+def test_full_size_configs_on_sampled_rows(fc, name):
+    w = synth_inputs.WORKLOADS[name]
+    x = synth_inputs.make_partials_device(w.n_src, w.tokens, w.hidden, w.seed, "cuda",
+                                          w.outlier_frac, w.outlier_gain)
+    rows = np.unique(np.concatenate([[0, 1, w.tokens - 1],
+                                     np.random.default_rng(1).integers(0, w.tokens, 61)]))
+    rows = rows[rows < w.tokens]
+    ridx = torch.from_numpy(rows).cuda()
+    stage1 = [fc.quantize(x[j], w.group, w.bits_in) for j in range(w.n_src)]
+    c = torch.stack([p[0] for p in stage1]); s = torch.stack([p[1] for p in stage1])
+    z = torch.stack([p[2] for p in stage1])
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
+    y = fc.dequantize(co, so, zo, w.hidden, w.group, w.bits_out)
+    y2 = fc.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+    xs = x[:, ridx].cpu().numpy()
+    oc, os_, oz = oracle_stage1(xs, w.group, w.bits_in)
+    assert_triplet((c[:, ridx].cpu().numpy(), s[:, ridx].cpu().numpy(), z[:, ridx].cpu().numpy()),
+                   (oc, os_, oz), name + " stage 1")
+    want = oracle.dequant_reduce_requant(oc, os_, oz, w.hidden, w.group, w.bits_in, w.bits_out)
+    assert_triplet((co[ridx].cpu().numpy(), so[ridx].cpu().numpy(), zo[ridx].cpu().numpy()), want,
+                   name + " fused")
+    wy = oracle.dequantize(*want, w.hidden, w.group, w.bits_out)
+    assert_f16(y[ridx].cpu().numpy(), wy, np.repeat(want[1], w.group, axis=1), name + " output")
+    # properties that hold at any size: every code in range is automatic for 4/8 bit fields;
+    # scales positive and finite, zero-points integral
+    assert bool((so > 0).all()) and bool(torch.isfinite(so).all())
+    assert bool((zo == torch.round(zo)).all())
