@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libfc.so")
+# FC_LIBRARY overrides the location of the shared library (e.g. a differently tuned build)
+_LIB_PATH = os.environ.get("FC_LIBRARY") or os.path.join(_HERE, "libfc.so")
 _lib = None
 
 FC_MAX_SRC = 8
