@@ -27,7 +27,7 @@ int check_shape(int64_t tokens, int64_t hidden, int group, int bits, int64_t *n_
 {
     if (bits != 4 && bits != 8) return FC_ERR_BITS;
     const int sh = log2_exact(group);
-    if (sh < 5 || sh > 11) return FC_ERR_GROUP;            // 32 .. 2048
+    if (sh < 5 || sh > 10) return FC_ERR_GROUP;            // 32 .. 1024
     if (tokens < 0 || hidden <= 0) return FC_ERR_SHAPE;
     if (hidden % group != 0) return FC_ERR_GROUP;
     if (hidden > kMaxElems || (tokens > 0 && tokens > kMaxElems / hidden)) return FC_ERR_SHAPE;
@@ -81,8 +81,8 @@ int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, in
     if (!x_f16 || !codes || !scales || !zeros) return FC_ERR_NULL;
     if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_quantize(bits, x_f16, n, group / 32, log2_exact(group), codes,
-                                          scales, zeros, static_cast<hipStream_t>(hip_stream)));
+    return hip_result(fc::launch_quantize(bits, x_f16, n, group, codes, scales, zeros,
+                                          static_cast<hipStream_t>(hip_stream)));
 }
 
 int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
@@ -121,8 +121,7 @@ int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_byt
     a.meta_stride = meta_src_stride_elems;
     a.n_src = n_src;
     a.n_elems = n;
-    a.lpg = group / 32;
-    a.group_shift = log2_exact(group);
+    a.group = group;
     a.codes_out = codes_out;
     a.scales_out = scales_out;
     a.zeros_out = zeros_out;
@@ -146,7 +145,7 @@ int fc_dequantize(const void *codes, const float *scales, const float *zeros,
     if (!codes || !scales || !zeros || !y_f16) return FC_ERR_NULL;
     if (!aligned16(codes) || !aligned16(scales) || !aligned16(zeros) || !aligned16(y_f16))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_dequantize(bits, codes, scales, zeros, n, log2_exact(group), y_f16,
+    return hip_result(fc::launch_dequantize(bits, codes, scales, zeros, n, group, y_f16,
                                             static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -205,7 +204,7 @@ const char *fc_strerror(int code)
     case FC_OK: return "success";
     case FC_ERR_NULL: return "a required pointer is NULL";
     case FC_ERR_BITS: return "bit-width must be 4 or 8";
-    case FC_ERR_GROUP: return "group must be a power of two in [32, 2048] that divides hidden";
+    case FC_ERR_GROUP: return "group must be a power of two in [32, 1024] that divides hidden";
     case FC_ERR_SHAPE: return "bad tokens / hidden / n_src / source stride";
     case FC_ERR_ALIGN: return "pointers and strides must be 16-byte aligned";
     case FC_ERR_WORKSPACE: return "workspace missing or too small";

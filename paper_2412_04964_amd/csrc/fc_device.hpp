@@ -2,24 +2,37 @@
 // path: the group quantizer (paper Appendix, Eq. 1-2), its inverse, and the fused
 // Dequantize x N -> ReduceSum -> FinegrainedQuantize body of Algorithm 1.
 //
-// Work decomposition (wave64): every lane owns 32 consecutive elements of the
-// flattened [tokens*hidden] volume, so a group of g elements is g/32 adjacent
-// lanes (4 lanes = one DPP quad for g = 128), a wavefront covers 2048 elements
-// and a 256-thread workgroup covers 8192.  32 elements are exactly one 128-bit
-// access of 4-bit codes, two of 8-bit codes and four of binary16 values.
-// The per-group min/max is reduced in-lane first and then across the lanes of
-// the group with DPP row operations; nothing goes through LDS or memory.
+// Work decomposition (wave64).  On the code side every lane owns exactly one
+// 128-bit access: EPL = 32 consecutive elements for 4-bit codes, 16 for 8-bit
+// codes.  A group of g elements is therefore LPG = g/EPL adjacent lanes (4 lanes
+// = one DPP quad for g = 128 at 4 bit), a wavefront covers 64*EPL elements and a
+// 256-thread workgroup four times that.  The per-group min/max is reduced in the
+// lane first and then across the LPG lanes with DPP row operations.
 //
-// Arithmetic contract (must match the header of include/fc.h operation by
+// Memory access.  Every global access instruction of the bulk streams is one
+// fully coalesced 128-bit-per-lane access (lane l of a wavefront touches bytes
+// [16 l, 16 l + 16) of a 1 KB span).  Where a lane needs more than 16 contiguous
+// bytes (binary16 values, 8-bit output of 32 elements) the wavefront's span is
+// staged in LDS as an exact image of global memory and the lane reads or writes
+// its contiguous part there.  Strided 16-byte pieces per lane, the obvious
+// alternative, cost 25 % of the streaming bandwidth on this part (measured) and
+// far more once the accesses are marked non-temporal.
+//
+// Arithmetic contract: must match the header of include/fc.h operation by
 // operation; the build passes -ffp-contract=off so that no product is fused
-// into a sum unless written as fmaf here).
+// into a sum unless written as fmaf here.
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <float.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace fc {
+
+constexpr int kBlockThreads = 256;                   // 4 wavefronts
+constexpr int kBlockWaves = kBlockThreads / 64;
 
 #ifdef FC_WAVES_PER_EU
 #define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(FC_WAVES_PER_EU)))
@@ -27,11 +40,12 @@ namespace fc {
 #define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads)
 #endif
 
-constexpr int kLaneElems = 32;                       // elements per lane
-constexpr int kBlockThreads = 256;                   // 4 wavefronts
-constexpr int kBlockElems = kLaneElems * kBlockThreads;
+// elements per lane for a given code width: one 128-bit access of codes
+constexpr int lane_elems(int bits) { return 128 / bits; }
+constexpr int block_elems(int bits) { return kBlockThreads * lane_elems(bits); }
 
 typedef uint32_t u32;
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
@@ -39,12 +53,12 @@ __device__ __forceinline__ h2 as_h2(u32 v) { return __builtin_bit_cast(h2, v); }
 __device__ __forceinline__ u32 as_u32(h2 v) { return __builtin_bit_cast(u32, v); }
 
 // ---------------------------------------------------------------------------
-// Buffer addressing.  Every global access goes through a raw buffer resource
-// whose base is the (wave-uniform) start of the workgroup's tile and whose
-// size is the number of bytes from there to the end of the array: the lane's
-// position is a 32-bit offset, no 64-bit address lives in vector registers,
-// and lanes beyond the end of the volume (the ragged last tile) read zeros and
-// have their stores dropped by the hardware range check.
+// Buffer addressing.  Bulk accesses go through a raw buffer resource whose base
+// is the (wave-uniform) start of the workgroup's tile and whose size is the
+// number of bytes from there to the end of the array: the lane's position is a
+// 32-bit offset, no 64-bit address lives in vector registers, and lanes beyond
+// the end of the volume (the ragged last tile) read zeros and have their stores
+// dropped by the hardware range check.
 // ---------------------------------------------------------------------------
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -60,31 +74,72 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, int64_t bytes_left
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, n, 0x00020000);
 }
 
-// Wait until at most `N` vector-memory operations of this wavefront are still
+// Wait until at most `n` vector-memory operations of this wavefront are still
 // outstanding (they complete in issue order).  The compiler does not order LDS
-// reads after buffer-to-LDS loads by itself, so the landing-zone reads below are
+// reads after buffer-to-LDS loads by itself, so reads of a landing zone are
 // fenced explicitly; the "memory" clobber keeps the compiler from moving any
-// memory access across the wait.
+// memory access across the wait.  `n` must be wave-uniform.
 #define FC_WAIT_VM_CASE(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
 __device__ __forceinline__ void wait_vmem_outstanding(int n)
 {
-    switch (n) {   // n is a compile-time constant after unrolling; at most 8 sources x 2 pieces
+    switch (n) {
         FC_WAIT_VM_CASE(1) FC_WAIT_VM_CASE(2) FC_WAIT_VM_CASE(3) FC_WAIT_VM_CASE(4) FC_WAIT_VM_CASE(5)
         FC_WAIT_VM_CASE(6) FC_WAIT_VM_CASE(7) FC_WAIT_VM_CASE(8) FC_WAIT_VM_CASE(9) FC_WAIT_VM_CASE(10)
-        FC_WAIT_VM_CASE(11) FC_WAIT_VM_CASE(12) FC_WAIT_VM_CASE(13) FC_WAIT_VM_CASE(14)
+        FC_WAIT_VM_CASE(11) FC_WAIT_VM_CASE(12) FC_WAIT_VM_CASE(13) FC_WAIT_VM_CASE(14) FC_WAIT_VM_CASE(15)
+        FC_WAIT_VM_CASE(16) FC_WAIT_VM_CASE(17) FC_WAIT_VM_CASE(18) FC_WAIT_VM_CASE(19) FC_WAIT_VM_CASE(20)
+        FC_WAIT_VM_CASE(21) FC_WAIT_VM_CASE(22) FC_WAIT_VM_CASE(23) FC_WAIT_VM_CASE(24) FC_WAIT_VM_CASE(25)
+        FC_WAIT_VM_CASE(26) FC_WAIT_VM_CASE(27) FC_WAIT_VM_CASE(28) FC_WAIT_VM_CASE(29) FC_WAIT_VM_CASE(30)
+        FC_WAIT_VM_CASE(31) FC_WAIT_VM_CASE(32) FC_WAIT_VM_CASE(33) FC_WAIT_VM_CASE(34) FC_WAIT_VM_CASE(35)
+        FC_WAIT_VM_CASE(36) FC_WAIT_VM_CASE(37) FC_WAIT_VM_CASE(38) FC_WAIT_VM_CASE(39) FC_WAIT_VM_CASE(40)
     default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
 }
 #undef FC_WAIT_VM_CASE
 
-__device__ __forceinline__ float load_f32(rsrc_t r, u32 byte_off)
+// 128-bit LDS read that the compiler's wait-count bookkeeping does not see.
+// (With an ordinary LDS load the compiler guards a landing-zone read by waiting
+// for ALL outstanding vector-memory operations in some control-flow shapes, and
+// by not waiting at all in others; the landing zone is therefore ordered by
+// hand: wait_vmem_outstanding before, lds_read_complete after.)  The value
+// returned must not be used before lds_read_complete(v) has been called.
+__device__ __forceinline__ u32x4 lds_read_b128_issue(const void *p)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
+    u32x4 v;
+    const u32 addr = (u32)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
 }
 
-__device__ __forceinline__ void store_f32(rsrc_t r, u32 byte_off, float v)
+// Waits for every LDS operation of the wavefront; `v` passes through so that
+// no use of it can be scheduled in front of the wait.
+__device__ __forceinline__ void lds_read_complete(u32x4 &v)
 {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(u32, v), r, byte_off, 0, 0);
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v) : : "memory");
+}
+
+// the compiler may not move memory operations across this point
+__device__ __forceinline__ void issue_order_fence() { asm volatile("" ::: "memory"); }
+
+// Pins the program position of the values in v[]: everything that produces them
+// is emitted before this point and everything that consumes them after it.
+// (Pure arithmetic is otherwise free to sink below later volatile statements,
+// which here would collect all landing-zone reads first and keep every
+// source's codes in registers at once.)  Generates no instruction.
+template <int N>
+__device__ __forceinline__ void pin_values(float (&v)[N])
+{
+    static_assert(N % 8 == 0, "pinned in groups of 8");
+#pragma unroll
+    for (int i = 0; i < N; i += 8)
+        asm volatile("" : "+v"(v[i]), "+v"(v[i + 1]), "+v"(v[i + 2]), "+v"(v[i + 3]), "+v"(v[i + 4]),
+                          "+v"(v[i + 5]), "+v"(v[i + 6]), "+v"(v[i + 7]));
+}
+
+// One coalesced 1 KB piece of a wavefront: lane l's 16 bytes at `off` (which
+// already contains 16*l) go to lds_piece + 16*l.
+__device__ __forceinline__ void dma_piece(rsrc_t r, u32 off, void *lds_piece)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds_piece, 16, off, 0, 0, kStreamPolicy);
 }
 
 // ---------------------------------------------------------------------------
@@ -97,8 +152,8 @@ __device__ __forceinline__ float dpp_read(float v)
         float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
-constexpr int kDppQuadXor1 = 0xB1;      // quad_perm:[1,0,3,2]
-constexpr int kDppQuadXor2 = 0x4E;      // quad_perm:[2,3,0,1]
+constexpr int kDppQuadXor1 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
 constexpr int kDppRowMirror = 0x140;      // lane i <-> 15-i inside each 16 lanes
 
@@ -162,11 +217,11 @@ __device__ __forceinline__ u32 encode(float x, float inv, float zf)
     return (u32)fminf(fmaxf(u, 0.0f), qmax);
 }
 
-// Fast packing of the lane's 32 codes (see quantize_and_store): Horner merge of
+// Fast packing of the lane's codes (see quantize_lane): Horner merge of
 // t = rint(x*inv), optionally capped at tmax = qmax - z, plus z on every digit.
-template <int BITS, bool CAP>
-__device__ __forceinline__ void pack_codes(const float (&v)[kLaneElems], float inv, float zf, float tmax,
-                                           u32 (&word)[kLaneElems * BITS / 32])
+template <int BITS, int EPL, bool CAP>
+__device__ __forceinline__ void pack_codes(const float (&v)[EPL], float inv, float zf, float tmax,
+                                           u32 (&word)[EPL * BITS / 32])
 {
     auto digit = [&](float x) {
         const float t = rintf(x * inv);
@@ -175,7 +230,7 @@ __device__ __forceinline__ void pack_codes(const float (&v)[kLaneElems], float i
     if constexpr (BITS == 4) {
         const float zc = zf * 4369.0f;               // z * (1 + 16 + 256 + 4096)
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < EPL / 8; ++w) {
             float t[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) t[i] = digit(v[8 * w + i]);
@@ -186,7 +241,7 @@ __device__ __forceinline__ void pack_codes(const float (&v)[kLaneElems], float i
     } else {
         const float zc = zf * 257.0f;                // z * (1 + 256)
 #pragma unroll
-        for (int w = 0; w < 8; ++w) {
+        for (int w = 0; w < EPL / 4; ++w) {
             float t[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] = digit(v[4 * w + i]);
@@ -197,49 +252,45 @@ __device__ __forceinline__ void pack_codes(const float (&v)[kLaneElems], float i
     }
 }
 
-// Quantize the lane's 32 fp32 values and store codes (+ the group's scale and
-// zero-point from the group's first lane).
+// FinegrainedQuantize of the lane's EPL fp32 values: packed code words plus the
+// group's scale and zero-point (identical in all lanes of the group).
 //
 // Packing, fast path (|z| <= 2048 in every lane of the wavefront): with
 // t = rint(x*inv) the code is q = clamp(t + z, 0, qmax).  t >= rint(mn*inv) = -z
 // because x >= mn and both the product and rint are monotone, so the lower clamp
 // never acts, and since t, z and qmax are small integers the upper clamp can be
-// applied to t: q = min(t, qmax - z) + z exactly.  Several codes are then merged
-// in fp32 by Horner steps (t3*16 + t2)*16 + ... , every partial sum an integer
-// below 2^24 and therefore exact, and z*(1 + 16 + 16^2 + 16^3) is added once.
+// applied to t: q = min(t, qmax - z) + z exactly; it is skipped altogether when
+// rint(mx*inv), the largest t of the group, does not exceed qmax - z anywhere in
+// the wavefront.  Several codes are then merged in fp32 by Horner steps
+// (t3*16 + t2)*16 + ... , every partial sum an integer below 2^24 and therefore
+// exact, and z*(1 + 16 + 16^2 + 16^3) is added once.
 // Otherwise each code is formed literally as in Eq. 2.
-// `codes`, `scales`, `zeros` address the workgroup's tile; `code_off` is the
-// lane's first output byte and `group_idx` the lane's group inside the tile.
-template <int BITS, int LPG>
-__device__ __forceinline__ void quantize_and_store(const float (&v)[kLaneElems], int lpg_rt,
-                                                   rsrc_t codes, u32 code_off,
-                                                   rsrc_t scales, rsrc_t zeros, u32 group_idx)
+template <int BITS, int EPL, int LPG>
+__device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
+                                              u32 (&word)[EPL * BITS / 32], float &s, float &zf)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
     float mn = v[0], mx = v[0];
 #pragma unroll
-    for (int i = 1; i < kLaneElems; ++i) {
+    for (int i = 1; i < EPL; ++i) {
         mn = fminf(mn, v[i]);
         mx = fmaxf(mx, v[i]);
     }
     group_minmax<LPG>(mn, mx, lpg_rt);
-    float s, inv, zf;
+    float inv;
     group_params<BITS>(mn, mx, s, inv, zf);
     const bool pack_fast = __builtin_amdgcn_ballot_w64(!(fabsf(zf) <= 2048.0f)) == 0;
-
-    u32 word[kLaneElems * BITS / 32];
     if (pack_fast) {
-        // every t of the group is <= rint(mx*inv); the cap is needed only if that exceeds qmax - z
         const float tmax = qmax - zf;
         const bool need_cap = __builtin_amdgcn_ballot_w64(rintf(mx * inv) > tmax) != 0;
         if (need_cap)
-            pack_codes<BITS, true>(v, inv, zf, tmax, word);
+            pack_codes<BITS, EPL, true>(v, inv, zf, tmax, word);
         else
-            pack_codes<BITS, false>(v, inv, zf, tmax, word);
+            pack_codes<BITS, EPL, false>(v, inv, zf, tmax, word);
     } else {
         constexpr int per_word = 32 / BITS;
 #pragma unroll
-        for (int w = 0; w < kLaneElems / per_word; ++w) {
+        for (int w = 0; w < EPL / per_word; ++w) {
             u32 acc = 0;
 #pragma unroll
             for (int i = 0; i < per_word; ++i)
@@ -247,16 +298,38 @@ __device__ __forceinline__ void quantize_and_store(const float (&v)[kLaneElems],
             word[w] = acc;
         }
     }
-    __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, codes, code_off, 0,
-                                           kStreamPolicy);
-    if constexpr (BITS == 8)
-        __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[4], word[5], word[6], word[7]}, codes,
-                                               code_off + 16, 0, kStreamPolicy);
-    const int lpg = LPG > 0 ? LPG : lpg_rt;
-    if ((threadIdx.x & (lpg - 1)) == 0) {
-        store_f32(scales, group_idx * 4, s);
-        store_f32(zeros, group_idx * 4, zf);
+}
+
+// Store the lane's code words.  `r` addresses the workgroup's tile of the code
+// array.  8 or 16 bytes per lane go out directly (coalesced); 32 bytes per lane
+// are first laid out in the wavefront's LDS scratch `img` (2 KB) as they will
+// sit in memory and then written as two coalesced 1 KB pieces.
+template <int OUT_BYTES>
+__device__ __forceinline__ void store_codes(const u32 *word, rsrc_t r, u32 wave, u32 lane, uint8_t *img)
+{
+    const u32 wave_off = wave * (64 * OUT_BYTES);
+    if constexpr (OUT_BYTES == 8) {
+        __builtin_amdgcn_raw_buffer_store_b64(u32x2{word[0], word[1]}, r, wave_off + lane * 8, 0,
+                                              kStreamPolicy);
+    } else if constexpr (OUT_BYTES == 16) {
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, r,
+                                               wave_off + lane * 16, 0, kStreamPolicy);
+    } else {
+        static_assert(OUT_BYTES == 32, "8, 16 or 32 code bytes per lane");
+        u32x4 *mine = reinterpret_cast<u32x4 *>(img + lane * 32);
+        mine[0] = u32x4{word[0], word[1], word[2], word[3]};
+        mine[1] = u32x4{word[4], word[5], word[6], word[7]};
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(img + k * 1024 + lane * 16);
+            __builtin_amdgcn_raw_buffer_store_b128(a, r, wave_off + k * 1024 + lane * 16, 0, kStreamPolicy);
+        }
     }
+}
+
+__device__ __forceinline__ void store_f32(rsrc_t r, u32 byte_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(u32, v), r, byte_off, 0, 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -269,7 +342,7 @@ __device__ __forceinline__ void quantize_and_store(const float (&v)[kLaneElems],
 // binary16 subtract gives the integer q-z for two codes at once.  All three
 // numbers are integers of magnitude <= 2048, hence exact in binary16, and
 // widening to fp32 is exact, so d is bit-identical to the fp32 (float)q - z.
-// Slow path: convert and subtract in fp32.
+// General path: convert and subtract in fp32.
 // ---------------------------------------------------------------------------
 struct ZeroConst {
     h2 c1024;   // (1024 + z, 1024 + z)
@@ -281,14 +354,22 @@ __device__ __forceinline__ bool zero_is_fast(float zf)
     return (zf == rintf(zf)) && (zf >= -1700.0f) && (zf <= 1000.0f);
 }
 
-__device__ __forceinline__ ZeroConst make_zero_const(float zf)
+// (half(1024 + z), half(64 + z)) packed in one word
+__device__ __forceinline__ u32 pack_zero_const(float zf)
 {
-    ZeroConst c;
-    const _Float16 a = (_Float16)(1024.0f + zf);
-    const _Float16 b = (_Float16)(64.0f + zf);
-    c.c1024 = h2{a, a};
-    c.c64 = h2{b, b};
-    return c;
+    h2 c;
+    c.x = (_Float16)(1024.0f + zf);
+    c.y = (_Float16)(64.0f + zf);
+    return as_u32(c);
+}
+
+__device__ __forceinline__ ZeroConst unpack_zero_const(u32 packed)
+{
+    const h2 c = as_h2(packed);
+    ZeroConst z;
+    z.c1024 = h2{c.x, c.x};
+    z.c64 = h2{c.y, c.y};
+    return z;
 }
 
 // (a & mask) | orv in one VALU operation.  The compiler splits this into two
@@ -320,11 +401,53 @@ __device__ __forceinline__ void bytes_minus_zero(u32 w, const ZeroConst &c, h2 (
     p[1] = as_h2(__builtin_amdgcn_perm(0x64006400u, w, 0x05030501u)) - c.c1024;   // (b1, b3)
 }
 
-// acc[i] = fma(q_i - z, s, acc[i]) for the lane's 32 codes of one source.
-// `w` holds the raw code words: 4 words (4 bit) or 8 words (8 bit).
+// d[e] = q_e - z (as fp32) for the lane's 128 bits of codes
 template <int BITS>
-__device__ __forceinline__ void accumulate_fast(const u32 *w, float s, const ZeroConst &c,
-                                                float (&acc)[kLaneElems])
+__device__ __forceinline__ void codes_minus_zero_fast(const u32 (&w)[4], const ZeroConst &c,
+                                                      float (&d)[128 / BITS])
+{
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 p[4];
+            nibbles_minus_zero(w[k], c, p);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                d[8 * k + i] = (float)p[i].x;
+                d[8 * k + 4 + i] = (float)p[i].y;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 p[2];
+            bytes_minus_zero(w[k], c, p);
+            d[4 * k + 0] = (float)p[0].x;
+            d[4 * k + 2] = (float)p[0].y;
+            d[4 * k + 1] = (float)p[1].x;
+            d[4 * k + 3] = (float)p[1].y;
+        }
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void codes_minus_zero_general(const u32 (&w)[4], float zf,
+                                                         float (&d)[128 / BITS])
+{
+    constexpr int per_word = 32 / BITS;
+    constexpr u32 mask = (1u << BITS) - 1u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < per_word; ++i)
+            d[per_word * k + i] = (float)((w[k] >> (BITS * i)) & mask) - zf;
+}
+
+// acc[e] = fma(q_e - z, s, acc[e]) for the lane's codes of one source.  The
+// widening of the binary16 difference folds into the multiply-add.
+template <int BITS>
+__device__ __forceinline__ void accumulate_fast(const u32 (&w)[4], float s, const ZeroConst &c,
+                                                float (&acc)[128 / BITS])
 {
     if constexpr (BITS == 4) {
 #pragma unroll
@@ -339,7 +462,7 @@ __device__ __forceinline__ void accumulate_fast(const u32 *w, float s, const Zer
         }
     } else {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 4; ++k) {
             h2 p[2];
             bytes_minus_zero(w[k], c, p);
             acc[4 * k + 0] = fmaf((float)p[0].x, s, acc[4 * k + 0]);
@@ -351,13 +474,13 @@ __device__ __forceinline__ void accumulate_fast(const u32 *w, float s, const Zer
 }
 
 template <int BITS>
-__device__ __forceinline__ void accumulate_general(const u32 *w, float s, float zf,
-                                                   float (&acc)[kLaneElems])
+__device__ __forceinline__ void accumulate_general(const u32 (&w)[4], float s, float zf,
+                                                   float (&acc)[128 / BITS])
 {
     constexpr int per_word = 32 / BITS;
     constexpr u32 mask = (1u << BITS) - 1u;
 #pragma unroll
-    for (int k = 0; k < kLaneElems / per_word; ++k)
+    for (int k = 0; k < 4; ++k)
 #pragma unroll
         for (int i = 0; i < per_word; ++i) {
             const float d = (float)((w[k] >> (BITS * i)) & mask) - zf;
@@ -366,18 +489,25 @@ __device__ __forceinline__ void accumulate_general(const u32 *w, float s, float 
 }
 
 // ---------------------------------------------------------------------------
-// Kernels.  One workgroup = 256 threads = 4 wavefronts = one tile of 8192
-// consecutive elements; wavefronts never synchronize with each other.
+// Kernels.  One workgroup = 256 threads = 4 wavefronts; wavefronts never
+// synchronize with each other (every LDS region is private to one wavefront).
 // ---------------------------------------------------------------------------
 
 // FinegrainedQuantize of binary16 input (Algorithm 1, first quantization).
+// One tile of 256*EPL elements per workgroup.  The wavefront's 64*EPL*2 input
+// bytes are fetched as coalesced 1 KB pieces straight into LDS (an image of
+// global memory) and each lane then reads its EPL contiguous values from there.
 template <int BITS, int LPG>
 __global__ FC_KERNEL_ATTRS void k_quantize(
     const uint16_t *__restrict__ x, int64_t n_elems, int lpg, int group_shift,
     uint8_t *__restrict__ codes, float *__restrict__ scales, float *__restrict__ zeros)
 {
-    const u32 tid = threadIdx.x;
-    const int64_t e_tile = (int64_t)blockIdx.x * kBlockElems;
+    constexpr int EPL = lane_elems(BITS);
+    constexpr int kPieces = EPL * 2 / 16;                       // 1 KB pieces per wavefront
+    __shared__ __attribute__((aligned(16))) uint8_t img[kBlockWaves][kPieces * 1024];
+
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const int64_t e_tile = (int64_t)blockIdx.x * block_elems(BITS);
     const int64_t g_tile = e_tile >> group_shift;
     const int64_t n_groups = n_elems >> group_shift;
     const rsrc_t rx = make_rsrc(x + e_tile, (n_elems - e_tile) * 2);
@@ -385,10 +515,16 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t rz = make_rsrc(zeros + g_tile, (n_groups - g_tile) * 4);
 
-    float v[kLaneElems];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rx, tid * 64 + 16 * k, 0, kStreamPolicy);
+    for (int k = 0; k < kPieces; ++k)
+        dma_piece(rx, wave * (kPieces * 1024) + k * 1024 + lane * 16, &img[wave][k * 1024]);
+    wait_vmem_outstanding(0);
+
+    float v[EPL];
+    const u32x4 *mine = reinterpret_cast<const u32x4 *>(&img[wave][lane * (EPL * 2)]);
+#pragma unroll
+    for (int k = 0; k < kPieces; ++k) {
+        const u32x4 a = mine[k];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const h2 p = as_h2(a[i]);
@@ -396,21 +532,33 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
             v[8 * k + 2 * i + 1] = (float)p.y;
         }
     }
-    quantize_and_store<BITS, LPG>(v, lpg, rc, tid * (kLaneElems * BITS / 8), rs, rz,
-                                  (tid * kLaneElems) >> group_shift);
+
+    u32 word[EPL * BITS / 32];
+    float s, zf;
+    quantize_lane<BITS, EPL, LPG>(v, lpg, word, s, zf);
+    store_codes<16>(word, rc, wave, lane, nullptr);
+    const int lpg_v = LPG > 0 ? LPG : lpg;
+    if ((tid & (lpg_v - 1)) == 0) {
+        const u32 gi = (tid * EPL) >> group_shift;
+        store_f32(rs, gi * 4, s);
+        store_f32(rz, gi * 4, zf);
+    }
 }
 
 // Dequantize x NSRC, ReduceSum, FinegrainedQuantize (Algorithm 1, loop body
 // between the two exchanges).  The fp32 sum lives in registers only.
 //
+// One tile of 256*EPL elements per workgroup, one wavefront tile per wavefront.
 // Fan-in staging: at wavefront start every lane issues, for each of the NSRC
-// sources, one (two for 8-bit codes) 128-bit buffer load that the memory
-// pipeline writes straight into the wavefront's LDS landing zone, bypassing the
-// vector registers.  All NSRC x 1 KB (2 KB) of a wavefront are therefore in
-// flight at once while its registers hold only the 32 accumulators and the
-// source currently being folded in, which keeps enough wavefronts resident per
-// SIMD to cover HBM latency.  Each source is then read back with ds_read_b128
-// (lane-contiguous, conflict-free) and accumulated.
+// sources, one 128-bit buffer load that the memory pipeline writes straight into
+// the wavefront's LDS landing zone (1 KB per source), bypassing the vector
+// registers.  All NSRC KB of a wavefront are in flight at once while its
+// registers hold only the accumulators and the source being folded in, which
+// keeps 8 wavefronts resident per SIMD.  Each source is read back with one
+// ds_read_b128 per lane (conflict-free) as soon as its load has retired.
+// The group scales / zero-points of the wavefront tile (NSRC x 64/LPG entries)
+// are spread over the lanes, checked and converted once, and passed to the
+// consuming lanes through a small LDS table.
 template <int BITS_IN, int BITS_OUT, int NSRC, int LPG>
 __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
@@ -418,183 +566,150 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
     int64_t n_elems, int lpg, int group_shift,
     uint8_t *__restrict__ codes_out, float *__restrict__ scales_out, float *__restrict__ zeros_out)
 {
-    constexpr int kLaneIn = kLaneElems * BITS_IN / 8;        // 16 or 32 bytes of codes per lane
-    constexpr int kPieces = kLaneIn / 16;                     // 128-bit pieces per lane
-    constexpr int kWords = kLaneElems * BITS_IN / 32;
-    constexpr int kWaveElems = 64 * kLaneElems;
+    constexpr int EPL = lane_elems(BITS_IN);
+    constexpr int kWaveElems = 64 * EPL;
+    constexpr int kTileElems = kBlockThreads * EPL;
+    constexpr int kOutBytes = EPL * BITS_OUT / 8;             // code bytes a lane writes: 8, 16 or 32
     constexpr int kMaxGw = LPG > 0 ? 64 / LPG : 8;            // groups per wavefront tile (upper bound)
-    constexpr int kMetaIters = (NSRC * kMaxGw + 63) / 64;
+    constexpr int K = (NSRC * kMaxGw + 63) / 64;              // table entries per lane
     struct MetaRec { float s; u32 z; };                       // z: packed halves (fast) or fp32 bits
-    __shared__ __attribute__((aligned(16))) uint8_t landing[kBlockThreads / 64][NSRC][kPieces][64 * 16];
-    __shared__ MetaRec meta[kBlockThreads / 64][NSRC * kMaxGw];
+
+    __shared__ __attribute__((aligned(16))) uint8_t landing[kBlockWaves][NSRC][1024];
+    __shared__ MetaRec meta[kBlockWaves][NSRC * kMaxGw];
+    __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kBlockWaves : 1]
+                                                            [kOutBytes == 32 ? 2048 : 16];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const int64_t e_tile = (int64_t)blockIdx.x * kBlockElems;
+    const int64_t e_tile = (int64_t)blockIdx.x * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
     const int64_t n_groups = n_elems >> group_shift;
-    const u32 group_idx = (tid * kLaneElems) >> group_shift;
-
-    // --- scale / zero-point table of the wavefront: its NSRC x gw entries are
-    // spread over the lanes (one or a few entries each), checked and converted
-    // once, and handed to the consuming lanes through LDS
-    const int gw_shift = 11 - group_shift;                    // log2(groups per wavefront tile)
-    const int gw = LPG > 0 ? 64 / LPG : (kWaveElems >> group_shift);
+    const int lpg_v = LPG > 0 ? LPG : lpg;
+    const int gw = 64 / lpg_v;                                // groups per wavefront tile
+    const int gw_shift = __builtin_ctz(gw);
     const int entries = NSRC * gw;
+
+    // --- table loads (small, first: vector-memory results return in issue order).
+    // entry idx = j * gw + g  <->  (source j, group g of the wavefront tile)
     const int64_t g_wave = (e_tile + (int64_t)wave * kWaveElems) >> group_shift;
-    float ms[kMetaIters], mz[kMetaIters];
-    bool ok = true;
+    float ms[K], mz[K];
 #pragma unroll
-    for (int it = 0; it < kMetaIters; ++it) {
-        const int idx = it * 64 + (int)lane;
+    for (int it = 0; it < K; ++it) {
+        int idx = it * 64 + (int)lane;
+        idx = idx < entries ? idx : 0;                        // surplus lanes re-read entry 0
         const int j = idx >> gw_shift, g = idx & (gw - 1);
-        ms[it] = 0.0f;
-        mz[it] = 0.0f;
-        if (idx < entries && g_wave + g < n_groups) {
-            const int64_t at = (int64_t)j * meta_stride + g_wave + g;
-            ms[it] = scales_in[at];
-            mz[it] = zeros_in[at];
-        }
-        ok = ok && zero_is_fast(mz[it]);
+        int64_t gi = g_wave + g;
+        gi = gi < n_groups ? gi : n_groups - 1;               // ragged tail: stay inside the array
+        const int64_t at = (int64_t)j * meta_stride + gi;
+        ms[it] = scales_in[at];
+        mz[it] = zeros_in[at];
     }
+    issue_order_fence();
 
     // --- codes: straight into the landing zone
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) {
         const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
                                     (n_elems - e_tile) * BITS_IN / 8);
-#pragma unroll
-        for (int p = 0; p < kPieces; ++p)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rc, (lds_void *)&landing[wave][j][p][0], 16,
-                                                     tid * kLaneIn + 16 * p, 0, 0, kStreamPolicy);
+        dma_piece(rc, tid * 16, &landing[wave][j][0]);
     }
+    issue_order_fence();
 
+    // --- table: check, convert, publish
+    bool ok = true;
+#pragma unroll
+    for (int it = 0; it < K; ++it) ok = ok && zero_is_fast(mz[it]);
     const bool all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
 #pragma unroll
-    for (int it = 0; it < kMetaIters; ++it) {
+    for (int it = 0; it < K; ++it) {
         const int idx = it * 64 + (int)lane;
         if (idx < entries) {
             MetaRec r;
             r.s = ms[it];
-            if (all_fast) {
-                h2 c;
-                c.x = (_Float16)(1024.0f + mz[it]);
-                c.y = (_Float16)(64.0f + mz[it]);
-                r.z = as_u32(c);
-            } else {
-                r.z = __builtin_bit_cast(u32, mz[it]);
-            }
+            r.z = all_fast ? pack_zero_const(mz[it]) : __builtin_bit_cast(u32, mz[it]);
             meta[wave][idx] = r;
         }
     }
-    const MetaRec *my_meta = &meta[wave][(lane * kLaneElems) >> group_shift];
+    const MetaRec *my_meta = &meta[wave][lane / lpg_v];
 
-    float acc[kLaneElems];
+    float acc[EPL];
 #pragma unroll
-    for (int i = 0; i < kLaneElems; ++i) acc[i] = 0.0f;
-
-    auto read_landing = [&](int j, u32 (&w)[kWords]) {
-        // source j's pieces are complete once no more than the pieces of the
-        // later sources (issued after it) are outstanding
-        wait_vmem_outstanding((NSRC - 1 - j) * kPieces);
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.0f;
+    // one pass over the sources; the fast / general choice is made once per
+    // tile so that the accumulators never cross a control-flow merge
+    auto fold_sources = [&](auto fast_tag) {
 #pragma unroll
-        for (int p = 0; p < kPieces; ++p) {
-            const u32x4 a = *reinterpret_cast<const u32x4 *>(&landing[wave][j][p][lane * 16]);
-            w[4 * p + 0] = a[0]; w[4 * p + 1] = a[1]; w[4 * p + 2] = a[2]; w[4 * p + 3] = a[3];
+        for (int j = 0; j < NSRC; ++j) {
+            // source j has landed once no more than the loads of the later
+            // sources (issued after it) are outstanding
+            wait_vmem_outstanding(NSRC - 1 - j);
+            u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+            const MetaRec r = my_meta[j * gw];
+            lds_read_complete(a);
+            const u32 w[4] = {a[0], a[1], a[2], a[3]};
+            if constexpr (decltype(fast_tag)::value)
+                accumulate_fast<BITS_IN>(w, r.s, unpack_zero_const(r.z), acc);
+            else
+                accumulate_general<BITS_IN>(w, r.s, __builtin_bit_cast(float, r.z), acc);
+            pin_values(acc);          // source j is folded in before source j+1 is waited for
         }
     };
+    if (all_fast)
+        fold_sources(std::true_type{});
+    else
+        fold_sources(std::false_type{});
 
-    if (all_fast) {
-#pragma unroll
-        for (int j = 0; j < NSRC; ++j) {
-            u32 w[kWords];
-            read_landing(j, w);
-            const MetaRec r = my_meta[j * gw];
-            const h2 c = as_h2(r.z);
-            ZeroConst zc;
-            zc.c1024 = h2{c.x, c.x};
-            zc.c64 = h2{c.y, c.y};
-            accumulate_fast<BITS_IN>(w, r.s, zc, acc);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < NSRC; ++j) {
-            u32 w[kWords];
-            read_landing(j, w);
-            const MetaRec r = my_meta[j * gw];
-            accumulate_general<BITS_IN>(w, r.s, __builtin_bit_cast(float, r.z), acc);
-        }
-    }
-
+    // --- requantize the sums and store
+    u32 word[EPL * BITS_OUT / 32];
+    float s, zf;
+    quantize_lane<BITS_OUT, EPL, LPG>(acc, lpg, word, s, zf);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t rz = make_rsrc(zeros_out + g_tile, (n_groups - g_tile) * 4);
-    quantize_and_store<BITS_OUT, LPG>(acc, lpg, rc, tid * (kLaneElems * BITS_OUT / 8), rs, rz, group_idx);
+    store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
+    if ((tid & (lpg_v - 1)) == 0) {
+        const u32 gi = (tid * EPL) >> group_shift;
+        store_f32(rs, gi * 4, s);
+        store_f32(rz, gi * 4, zf);
+    }
 }
 
 // Dequantize to binary16 (Algorithm 1, last step): y = half_rne((q - z) * s).
+// One tile of 256*EPL elements per workgroup; the EPL halves of a lane are laid
+// out in the wavefront's LDS image and leave as coalesced 1 KB pieces.
 template <int BITS>
 __global__ FC_KERNEL_ATTRS void k_dequantize(
     const uint8_t *__restrict__ codes, const float *__restrict__ scales,
     const float *__restrict__ zeros, int64_t n_elems, int group_shift, uint16_t *__restrict__ y)
 {
-    constexpr int kWords = kLaneElems * BITS / 32;
-    const u32 tid = threadIdx.x;
-    const int64_t e_tile = (int64_t)blockIdx.x * kBlockElems;
+    constexpr int EPL = lane_elems(BITS);
+    constexpr int kPieces = EPL * 2 / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t img[kBlockWaves][kPieces * 1024];
+
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const int64_t e_tile = (int64_t)blockIdx.x * block_elems(BITS);
     const int64_t g_tile = e_tile >> group_shift;
     const int64_t n_groups = n_elems >> group_shift;
-    const u32 group_idx = (tid * kLaneElems) >> group_shift;
+    const u32 gi = (tid * EPL) >> group_shift;
     const rsrc_t rc = make_rsrc(codes + e_tile * BITS / 8, (n_elems - e_tile) * BITS / 8);
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t rz = make_rsrc(zeros + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t ry = make_rsrc(y + e_tile, (n_elems - e_tile) * 2);
 
-    const float s = load_f32(rs, group_idx * 4);
-    const float zf = load_f32(rz, group_idx * 4);
-    u32 w[kWords];
-#pragma unroll
-    for (int p = 0; p < kWords / 4; ++p) {
-        const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * (kWords * 4) + 16 * p, 0, kStreamPolicy);
-        w[4 * p + 0] = a[0]; w[4 * p + 1] = a[1]; w[4 * p + 2] = a[2]; w[4 * p + 3] = a[3];
-    }
+    const float s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
+    const float zf = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rz, gi * 4, 0, 0));
+    const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamPolicy);
+    const u32 w[4] = {a[0], a[1], a[2], a[3]};
 
-    float d[kLaneElems];
+    float d[EPL];
     const bool wave_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0;
-    if (wave_fast) {
-        const ZeroConst c = make_zero_const(zf);
-        if (BITS == 4) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                h2 p[4];
-                nibbles_minus_zero(w[k % kWords], c, p);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    d[8 * k + i] = (float)p[i].x;
-                    d[8 * k + 4 + i] = (float)p[i].y;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                h2 p[2];
-                bytes_minus_zero(w[k % kWords], c, p);
-                d[4 * k + 0] = (float)p[0].x;
-                d[4 * k + 2] = (float)p[0].y;
-                d[4 * k + 1] = (float)p[1].x;
-                d[4 * k + 3] = (float)p[1].y;
-            }
-        }
-    } else {
-        constexpr int per_word = 32 / BITS;
-        constexpr u32 mask = (1u << BITS) - 1u;
-#pragma unroll
-        for (int k = 0; k < kWords; ++k)
-#pragma unroll
-            for (int i = 0; i < per_word; ++i)
-                d[per_word * k + i] = (float)((w[k] >> (BITS * i)) & mask) - zf;
-    }
+    if (wave_fast)
+        codes_minus_zero_fast<BITS>(w, unpack_zero_const(pack_zero_const(zf)), d);
+    else
+        codes_minus_zero_general<BITS>(w, zf, d);
 
+    u32x4 *mine = reinterpret_cast<u32x4 *>(&img[wave][lane * (EPL * 2)]);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kPieces; ++k) {
         u32x4 out;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -603,7 +718,13 @@ __global__ FC_KERNEL_ATTRS void k_dequantize(
             p.y = (_Float16)(d[8 * k + 2 * i + 1] * s);
             out[i] = as_u32(p);
         }
-        __builtin_amdgcn_raw_buffer_store_b128(out, ry, tid * 64 + 16 * k, 0, kStreamPolicy);
+        mine[k] = out;
+    }
+#pragma unroll
+    for (int k = 0; k < kPieces; ++k) {
+        const u32x4 o = *reinterpret_cast<const u32x4 *>(&img[wave][k * 1024 + lane * 16]);
+        __builtin_amdgcn_raw_buffer_store_b128(o, ry, wave * (kPieces * 1024) + k * 1024 + lane * 16, 0,
+                                               kStreamPolicy);
     }
 }
 

@@ -16,24 +16,26 @@ namespace fc {
 template <int NSRC, int LPG>
 static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 {
-    const int64_t blocks = (a.n_elems + kBlockElems - 1) / kBlockElems;
+    const int64_t tile = block_elems(FC_BITS_IN);
+    const int64_t blocks = (a.n_elems + tile - 1) / tile;
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
         <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
-            static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
-            a.meta_stride, a.n_elems, a.lpg, a.group_shift, static_cast<uint8_t *>(a.codes_out),
-            a.scales_out, a.zeros_out);
+        static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
+        a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+        static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
     return hipGetLastError();
 }
 
-// groups of 32, 64 and 128 (1, 2, 4 lanes) get their own instantiation; larger
+// groups spanning 1, 2, 4 or 8 lanes get their own instantiation; larger
 // groups share one that reads the lane count at run time
 template <int NSRC>
 static hipError_t launch_n(const FusedArgs &a, hipStream_t stream)
 {
-    switch (a.lpg) {
+    switch (a.group / lane_elems(FC_BITS_IN)) {
     case 1: return launch_nl<NSRC, 1>(a, stream);
     case 2: return launch_nl<NSRC, 2>(a, stream);
     case 4: return launch_nl<NSRC, 4>(a, stream);
+    case 8: return launch_nl<NSRC, 8>(a, stream);
     default: return launch_nl<NSRC, 0>(a, stream);
     }
 }

@@ -7,13 +7,13 @@
 
 namespace fc {
 
-// n_elems = tokens*hidden (a multiple of the group size); lpg = group/32 lanes
-// per group; group_shift = log2(group).  All pointers are device pointers.
-hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int lpg, int group_shift,
+// n_elems = tokens*hidden (a multiple of `group`, which is a power of two in
+// [32, 1024]).  All pointers are device pointers.
+hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int group,
                            void *codes, float *scales, float *zeros, hipStream_t stream);
 
 hipError_t launch_dequantize(int bits, const void *codes, const float *scales, const float *zeros,
-                             int64_t n_elems, int group_shift, void *y_f16, hipStream_t stream);
+                             int64_t n_elems, int group, void *y_f16, hipStream_t stream);
 
 struct FusedArgs {
     const void *codes_in;
@@ -23,8 +23,7 @@ struct FusedArgs {
     int64_t meta_stride;
     int n_src;
     int64_t n_elems;
-    int lpg;
-    int group_shift;
+    int group;
     void *codes_out;
     float *scales_out;
     float *zeros_out;
@@ -35,5 +34,12 @@ hipError_t launch_fused_4_4(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_4_8(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_8_4(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_8_8(const FusedArgs &a, hipStream_t stream);
+
+inline int log2_int(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
 
 }  // namespace fc
