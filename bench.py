@@ -53,13 +53,17 @@ def dequantize_bytes(w) -> int:
 
 
 def load_traffic(name):
-    """HBM bytes per fused launch measured with rocprofv3 --pmc (committed summary)."""
-    p = os.path.join(ROOT, "profiles", "traffic_%s.json" % name)
-    if os.path.exists(p):
-        try:
-            return json.load(open(p)).get("fused_hbm_bytes_per_launch")
-        except Exception:
-            return None
+    """HBM bytes per fused launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the
+    committed, calibrated summary under profiles/); None when no measurement exists."""
+    p = os.path.join(ROOT, "profiles", "traffic_%s.txt" % name)
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith("fused_hbm_bytes_per_launch"):
+            try:
+                return int(line.split("=")[1])
+            except ValueError:
+                return None
     return None
 
 
