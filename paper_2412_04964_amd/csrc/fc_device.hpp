@@ -191,19 +191,38 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lpg_rt)
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 1: scale, reciprocal and zero-point of one group from its min and max
+// Eq. 1: scale, reciprocal and zero-point of one group from its min and max.
+//
+// The two IEEE divisions are evaluated by short sequences that were checked on
+// gfx950 against the `/` operator for every positive fp32 bit pattern:
+//   r / qmax (qmax = 15, 255):  q0 = r*c,  e = fma(-qmax, q0, r),  q = fma(e, c, q0)
+//       with c = RN(1/qmax): equal to the correctly rounded quotient for ALL
+//       positive r, subnormal and huge included;
+//   1 / s:  y0 = v_rcp_f32(s),  e = fma(-s, y0, 1),  y = fma(e, y0, y0): equal to
+//       the correctly rounded reciprocal for all s in [2^-126, 2^126]; s is never
+//       below FLT_MIN here, and a wavefront holding an s above 2^100 takes the
+//       ordinary division.
 // ---------------------------------------------------------------------------
 template <int BITS>
 __device__ __forceinline__ void group_params(float mn, float mx, float &s, float &inv, float &zf)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
+    constexpr float c = 1.0f / qmax;
     const float r = mx - mn;
-    s = r / qmax;
+    const float q0 = r * c;
+    const float e = fmaf(-qmax, q0, r);
+    s = fmaf(e, c, q0);                    // == r / qmax
     if (!(s >= FLT_MIN)) {                 // constant (or nearly constant) group
         const float a = fabsf(mn);
         s = (a >= FLT_MIN) ? a : 1.0f;
     }
-    inv = 1.0f / s;
+    if (__builtin_amdgcn_ballot_w64(!(s <= 0x1p100f)) == 0) {
+        const float y0 = __builtin_amdgcn_rcpf(s);
+        const float e1 = fmaf(-s, y0, 1.0f);
+        inv = fmaf(e1, y0, y0);            // == 1 / s
+    } else {
+        inv = 1.0f / s;
+    }
     zf = 0.0f - rintf(mn * inv);
 }
 

@@ -233,6 +233,46 @@ def test_fused_source_stride_with_padding(fc):
     assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "padded stride")
 
 
+def _clamp_case_groups(group, n_groups, rng):
+    """fp16 groups whose largest rounded value exceeds qmax - z by one step (the upper clamp of
+    Eq. 2 acts): range 7.5 with both ends on .5 ties, so s = 0.5 (4 bit) and the ends round apart."""
+    rows = []
+    for k in range(n_groups):
+        off = float(rng.integers(-40, 40))
+        body = rng.uniform(-1.5, 5.5, size=group)
+        body[rng.integers(0, group)] = -1.75
+        body[rng.integers(0, group - 1) + (1 if body[0] == -1.75 else 0)] = 5.75
+        if not (body == -1.75).any():
+            body[0] = -1.75
+        rows.append(body + off)
+    return np.concatenate(rows).astype(np.float16)
+
+
+@pytest.mark.parametrize("group", [32, 128])
+def test_upper_clamp_is_exercised(fc, group):
+    rng = np.random.default_rng(group)
+    x = np.stack([_clamp_case_groups(group, 4096 // group, rng) for _ in range(8)])
+    want = oracle.quantize(x, group, 4)
+    # the case set really triggers the clamp: some group's top code comes from t + z = 16
+    xf = x.astype(np.float32).reshape(8, -1, group)
+    t_top = np.rint(xf.max(-1) * (np.float32(1) / want[1])) + want[2]
+    assert (t_top > 15).any()
+    assert_triplet(gpu_quantize(fc, x, group, 4), want, "clamp quantize g=%d" % group)
+    # same through the fused kernel: one 8-bit source with scale 0.25 and zero-point 100 whose codes
+    # 93..123 dequantize exactly to -1.75..5.75, so the requantized sums hit the clamp as well
+    t, h = 8, 4096
+    codes = rng.integers(94, 123, size=(1, t, h), dtype=np.uint8)
+    cg = codes.reshape(1, t, h // group, group)
+    cg[..., 3] = 93
+    cg[..., 17] = 123
+    s = np.full((1, t, h // group), 0.25, np.float32)
+    z = np.full((1, t, h // group), 100.0, np.float32)
+    want_f = oracle.dequant_reduce_requant(codes, s, z, h, group, 8, 4)
+    acc = oracle.dequant_reduce_f32(codes, s, z, h, group, 8).reshape(t, h // group, group)
+    assert (np.rint(acc.max(-1) * (np.float32(1) / want_f[1])) + want_f[2] > 15).all()
+    assert_triplet(gpu_fused(fc, codes, s, z, h, group, 8, 4), want_f, "clamp fused g=%d" % group)
+
+
 # --------------------------------------------------------------------------- #
 # fc_dequantize
 # --------------------------------------------------------------------------- #
