@@ -12,7 +12,8 @@
  *
  * Quantizer (Appendix "Quantization Fundamentals", Eq. 1-2, asymmetric; groups
  * of `group` consecutive elements along `hidden`, Section 3.2.1), in fp32 with
- * round-to-nearest-even, evaluated exactly in this order for every group:
+ * round-to-nearest-even.  Results are bit-identical to evaluating, for every
+ * group, exactly these operations in this order:
  *     mn, mx   = min, max of the group
  *     s        = (mx - mn) / (2^bits - 1)          one IEEE divide
  *     if !(s >= FLT_MIN):  s = |mn| >= FLT_MIN ? |mn| : 1       (constant group)
@@ -83,7 +84,7 @@ enum {
  *   zeros   out  float [tokens, hidden/group]
  */
 FC_API int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
-                void *codes, float *scales, float *zeros, void *hip_stream);
+                       void *codes, float *scales, float *zeros, void *hip_stream);
 
 /*
  * The body of Algorithm 1 between the two exchanges, fused: Dequantize each of
@@ -102,20 +103,20 @@ FC_API int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int gr
  *   codes_out, scales_out, zeros_out   out, as in fc_quantize with bits_out.
  */
 FC_API int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
-                              const float *scales_in, const float *zeros_in,
-                              int64_t meta_src_stride_elems,
-                              int n_src, int64_t tokens, int64_t hidden, int group,
-                              int bits_in, int bits_out,
-                              void *codes_out, float *scales_out, float *zeros_out,
-                              void *hip_stream);
+                                     const float *scales_in, const float *zeros_in,
+                                     int64_t meta_src_stride_elems,
+                                     int n_src, int64_t tokens, int64_t hidden, int group,
+                                     int bits_in, int bits_out,
+                                     void *codes_out, float *scales_out, float *zeros_out,
+                                     void *hip_stream);
 
 /*
  * Dequantize of Algorithm 1 (last call): y = binary16_rne((q - z) * s).
  * Values beyond the binary16 range become infinities.
  */
 FC_API int fc_dequantize(const void *codes, const float *scales, const float *zeros,
-                  int64_t tokens, int64_t hidden, int group, int bits,
-                  void *y_f16, void *hip_stream);
+                         int64_t tokens, int64_t hidden, int group, int bits,
+                         void *y_f16, void *hip_stream);
 
 /*
  * Algorithm 1 end to end on one device with identity exchanges:
@@ -128,12 +129,12 @@ FC_API int fc_dequantize(const void *codes, const float *scales, const float *ze
  *              bytes, 16-byte aligned; contents on return are unspecified.
  */
 FC_API int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
-                     int group, int bits_rs, int bits_ag, void *y_f16,
-                     void *workspace, size_t workspace_bytes, void *hip_stream);
+                            int group, int bits_rs, int bits_ag, void *y_f16,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes fc_allreduce_sim needs; 0 if the arguments are invalid. */
 FC_API size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
-                                        int bits_rs, int bits_ag);
+                                               int bits_rs, int bits_ag);
 
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);
