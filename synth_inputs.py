@@ -36,13 +36,15 @@ class Workload:
         return self.tokens * self.hidden
 
 
-# The five configurations the benchmark contract names.
+# The five configurations the benchmark contract names, plus the paper's mixed-precision
+# "INT6" setting (4 bit before the reduce, 8 bit before the gather; Section 3.2.3) at the headline shape.
 WORKLOADS = {
     "tiny": Workload("tiny", 2, 16, 4096, 8, 8, 128, outlier_frac=0.0),
     "llama3_8b_prefill": Workload("llama3_8b_prefill", 4, 8192, 4096, 8, 8, 128),
     "llama3_70b_prefill": Workload("llama3_70b_prefill", 4, 8192, 8192, 4, 4, 128),
     "wide_fanin": Workload("wide_fanin", 8, 8192, 8192, 4, 4, 64),
     "decode": Workload("decode", 8, 8, 8192, 8, 8, 128),
+    "llama3_70b_prefill_int6": Workload("llama3_70b_prefill_int6", 4, 8192, 8192, 4, 8, 128),
 }
 
 
