@@ -57,9 +57,22 @@ def lib() -> ctypes.CDLL:
         L.fc_ref_dequant_reduce_requant.argtypes = [vp, i64, vp, vp, i64, i32, i64, i64, i32, i32,
                                                     i32, vp, vp, vp]
         L.fc_ref_allreduce_sim.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp]
+        L.fc_ref_quantize_group_sym_f32.restype = None
+        L.fc_ref_quantize_group_sym_f32.argtypes = [vp, i32, i32, vp, vp]
+        L.fc_ref_quantize_sym_f32.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.fc_ref_quantize_sym.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.fc_ref_dequantize_sym_f32.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+        L.fc_ref_dequantize_sym.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+        L.fc_ref_dequant_reduce_sym_f32.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, vp]
+        L.fc_ref_dequant_reduce_requant_sym.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32,
+                                                        vp, vp]
+        L.fc_ref_allreduce_sim_sym.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp]
         for name in ("fc_ref_quantize_f32", "fc_ref_quantize", "fc_ref_dequantize_f32",
                      "fc_ref_dequantize", "fc_ref_dequant_reduce_f32",
-                     "fc_ref_dequant_reduce_requant", "fc_ref_allreduce_sim"):
+                     "fc_ref_dequant_reduce_requant", "fc_ref_allreduce_sim",
+                     "fc_ref_quantize_sym_f32", "fc_ref_quantize_sym", "fc_ref_dequantize_sym_f32",
+                     "fc_ref_dequantize_sym", "fc_ref_dequant_reduce_sym_f32",
+                     "fc_ref_dequant_reduce_requant_sym", "fc_ref_allreduce_sim_sym"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -184,4 +197,91 @@ def allreduce_sim(x_f16, group: int, bits_rs: int, bits_ag: int):
     n, t, h = x.shape
     y = np.zeros((t, h), np.uint16)
     _chk(lib().fc_ref_allreduce_sim(_p(x), n, t, h, group, bits_rs, bits_ag, _p(y)), "allreduce_sim")
+    return y.view(np.float16)
+
+
+# --------------------------------------------------------------------------- #
+# symmetric variant (Eq. 3-4): signed codes in two's complement, scales only
+# --------------------------------------------------------------------------- #
+
+def quantize_group_sym_f32(x, bits: int):
+    """Eq. 3-4 on one group of fp32 values -> (signed codes int8[g] unpacked, scale)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    q = np.zeros(x.size, np.int8)
+    s = np.zeros(1, np.float32)
+    lib().fc_ref_quantize_group_sym_f32(_p(x), x.size, bits, _p(q), _p(s))
+    return q, s[0]
+
+
+def quantize_sym_f32(x, group: int, bits: int):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    t, h = x.shape
+    _chk(0 if (h % group == 0 and bits in (4, 8)) else -1, "quantize_sym_f32")
+    c, s, _ = _alloc_q(t, h, group, bits)
+    _chk(lib().fc_ref_quantize_sym_f32(_p(x), t, h, group, bits, _p(c), _p(s)), "quantize_sym_f32")
+    return c, s
+
+
+def quantize_sym(x_f16, group: int, bits: int):
+    x = _as_u16(x_f16)
+    t, h = x.shape
+    _chk(0 if (h % group == 0 and bits in (4, 8)) else -1, "quantize_sym")
+    c, s, _ = _alloc_q(t, h, group, bits)
+    _chk(lib().fc_ref_quantize_sym(_p(x), t, h, group, bits, _p(c), _p(s)), "quantize_sym")
+    return c, s
+
+
+def dequantize_sym_f32(codes, scales, hidden: int, group: int, bits: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequantize_sym_f32(_p(codes), _p(scales), t, hidden, group, bits, _p(y)),
+         "dequantize_sym_f32")
+    return y
+
+
+def dequantize_sym(codes, scales, hidden: int, group: int, bits: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.uint16)
+    _chk(lib().fc_ref_dequantize_sym(_p(codes), _p(scales), t, hidden, group, bits, _p(y)),
+         "dequantize_sym")
+    return y.view(np.float16)
+
+
+def _stacked_sym(codes_in, scales_in):
+    c = np.ascontiguousarray(codes_in, np.uint8)
+    s = np.ascontiguousarray(scales_in, np.float32)
+    if c.ndim != 3 or s.ndim != 3 or s.shape[0] != c.shape[0]:
+        raise ValueError("expected codes [N,T,bytes], scales [N,T,groups]")
+    return c, s
+
+
+def dequant_reduce_sym_f32(codes_in, scales_in, hidden: int, group: int, bits_in: int):
+    c, s = _stacked_sym(codes_in, scales_in)
+    n, t = c.shape[0], c.shape[1]
+    acc = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequant_reduce_sym_f32(_p(c), c[0].nbytes, _p(s), s[0].size, n, t, hidden, group,
+                                             bits_in, _p(acc)), "dequant_reduce_sym_f32")
+    return acc
+
+
+def dequant_reduce_requant_sym(codes_in, scales_in, hidden: int, group: int, bits_in: int, bits_out: int):
+    c, s = _stacked_sym(codes_in, scales_in)
+    n, t = c.shape[0], c.shape[1]
+    co, so, _ = _alloc_q(t, hidden, group, bits_out)
+    _chk(lib().fc_ref_dequant_reduce_requant_sym(_p(c), c[0].nbytes, _p(s), s[0].size, n, t, hidden,
+                                                 group, bits_in, bits_out, _p(co), _p(so)),
+         "dequant_reduce_requant_sym")
+    return co, so
+
+
+def allreduce_sim_sym(x_f16, group: int, bits_rs: int, bits_ag: int):
+    x = _as_u16(x_f16)
+    n, t, h = x.shape
+    y = np.zeros((t, h), np.uint16)
+    _chk(lib().fc_ref_allreduce_sim_sym(_p(x), n, t, h, group, bits_rs, bits_ag, _p(y)),
+         "allreduce_sim_sym")
     return y.view(np.float16)

@@ -36,6 +36,14 @@
  *       dropped in the listing) and the sum has N terms;
  *   R8  INT4 codes are packed two per byte in linear order, element 2k in the
  *       low nibble and element 2k+1 in the high nibble.
+ * Symmetric variant (Appendix, Eq. 3-4; the paper's INT8_Sym / INT4_Sym ablation
+ * rows): the fc_ref_*_sym functions at the end of this file, with readings
+ *   S1  rounding and the per-group reciprocal as R1 and R4;
+ *   S2  s = max|X| / (2^(n-1) - 1) in fp32; a group whose s would be below
+ *       FLT_MIN (in particular the all-zero group) takes s = 1, all codes 0;
+ *   S3  codes are signed, clamped to [-2^(n-1), 2^(n-1)-1] as Eq. 4 says, and
+ *       stored in two's complement in the same packing as R8;
+ *   S4  Dequantize is x^ = q * s; the N-way sum is acc = fma(q_j, s_j, acc).
  * Domain: finite inputs.  NaN / Inf inputs: parity unpinned.
  *
  * Build: cc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
@@ -318,5 +326,184 @@ int fc_ref_allreduce_sim(const uint16_t *x_f16, int n_src, int64_t tokens, int64
     if (rc == FC_REF_OK)
         rc = fc_ref_dequantize(c2, s2, z2, tokens, hidden, group, bits_ag, y_f16);
     free(c1); free(s1); free(z1); free(c2); free(s2); free(z2);
+    return rc;
+}
+
+/* ======================================================================== */
+/* Symmetric quantization (Appendix, Eq. 3-4) -- readings S1-S4 above.       */
+/* ======================================================================== */
+
+/* Eq. 3-4 on ONE group.  q: g signed codes, one per byte (not packed). */
+void fc_ref_quantize_group_sym_f32(const float *x, int g, int bits, int8_t *q, float *scale)
+{
+    const float qm = (float)((1 << (bits - 1)) - 1);          /* 2^(n-1) - 1 */
+    const float lo = -(float)(1 << (bits - 1));               /* -2^(n-1)   */
+    float amax = 0.0f;
+    for (int k = 0; k < g; ++k) {
+        const float a = fabsf(x[k]);
+        if (a > amax) amax = a;
+    }
+    float s = amax / qm;                                      /* Eq. 3 */
+    if (!(s >= FLT_MIN)) s = 1.0f;                            /* S2 */
+    const float inv = 1.0f / s;
+    for (int k = 0; k < g; ++k) {
+        float t = rintf(x[k] * inv);                          /* Eq. 4: round(X / s) */
+        if (t < lo) t = lo;                                   /*        clamp        */
+        if (t > qm) t = qm;
+        q[k] = (int8_t)t;
+    }
+    *scale = s;
+}
+
+static void pack_row_signed(const int8_t *q, int64_t hidden, int bits, uint8_t *dst)
+{
+    if (bits == 8) {
+        for (int64_t k = 0; k < hidden; ++k) dst[k] = (uint8_t)q[k];
+    } else {
+        for (int64_t k = 0; k < hidden / 2; ++k)
+            dst[k] = (uint8_t)((q[2 * k] & 0x0F) | ((q[2 * k + 1] & 0x0F) << 4));
+    }
+}
+
+static int signed_code_at(const uint8_t *row, int64_t h, int bits)
+{
+    if (bits == 8) return (int)(int8_t)row[h];
+    const uint8_t b = row[h / 2];
+    const int n = (h & 1) ? (b >> 4) : (b & 0x0F);
+    return n >= 8 ? n - 16 : n;                               /* two's complement nibble */
+}
+
+int fc_ref_quantize_sym_f32(const float *x, int64_t tokens, int64_t hidden, int group, int bits,
+                            uint8_t *codes, float *scales)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x || !codes || !scales) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    int8_t *q = (int8_t *)malloc((size_t)hidden);
+    if (!q) return FC_REF_NO_MEM;
+    for (int64_t t = 0; t < tokens; ++t) {
+        for (int64_t c = 0; c < gpr; ++c)
+            fc_ref_quantize_group_sym_f32(x + t * hidden + c * group, group, bits, q + c * group,
+                                          &scales[t * gpr + c]);
+        pack_row_signed(q, hidden, bits, codes + t * row_bytes);
+    }
+    free(q);
+    return FC_REF_OK;
+}
+
+int fc_ref_quantize_sym(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                        uint8_t *codes, float *scales)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x_f16 || !codes || !scales) return FC_REF_BAD_ARG;
+    float *xf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!xf) return FC_REF_NO_MEM;
+    for (int64_t i = 0; i < tokens * hidden; ++i) xf[i] = fc_ref_half_to_float(x_f16[i]);
+    const int rc = fc_ref_quantize_sym_f32(xf, tokens, hidden, group, bits, codes, scales);
+    free(xf);
+    return rc;
+}
+
+/* x^ = q * s (S4), fp32 */
+int fc_ref_dequantize_sym_f32(const uint8_t *codes, const float *scales,
+                              int64_t tokens, int64_t hidden, int group, int bits, float *y)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !y) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h)
+            y[t * hidden + h] = (float)signed_code_at(codes + t * row_bytes, h, bits)
+                                * scales[t * gpr + h / group];
+    return FC_REF_OK;
+}
+
+int fc_ref_dequantize_sym(const uint8_t *codes, const float *scales,
+                          int64_t tokens, int64_t hidden, int group, int bits, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !y_f16) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h)
+            y_f16[t * hidden + h] = fc_ref_float_to_half(
+                (float)signed_code_at(codes + t * row_bytes, h, bits) * scales[t * gpr + h / group]);
+    return FC_REF_OK;
+}
+
+int fc_ref_dequant_reduce_sym_f32(const uint8_t *codes_in, int64_t codes_stride,
+                                  const float *scales_in, int64_t meta_stride,
+                                  int n_src, int64_t tokens, int64_t hidden, int group, int bits_in,
+                                  float *acc)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes_in || !scales_in || !acc) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits_in / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            float a = 0.0f;
+            for (int j = 0; j < n_src; ++j) {
+                const uint8_t *row = codes_in + (int64_t)j * codes_stride + t * row_bytes;
+                a = fmaf((float)signed_code_at(row, h, bits_in),
+                         scales_in[(int64_t)j * meta_stride + gi], a);
+            }
+            acc[t * hidden + h] = a;
+        }
+    return FC_REF_OK;
+}
+
+int fc_ref_dequant_reduce_requant_sym(const uint8_t *codes_in, int64_t codes_stride,
+                                      const float *scales_in, int64_t meta_stride,
+                                      int n_src, int64_t tokens, int64_t hidden, int group,
+                                      int bits_in, int bits_out,
+                                      uint8_t *codes_out, float *scales_out)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || !check_shape(tokens, hidden, group, bits_out)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    float *acc = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!acc) return FC_REF_NO_MEM;
+    int rc = fc_ref_dequant_reduce_sym_f32(codes_in, codes_stride, scales_in, meta_stride, n_src,
+                                           tokens, hidden, group, bits_in, acc);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_quantize_sym_f32(acc, tokens, hidden, group, bits_out, codes_out, scales_out);
+    free(acc);
+    return rc;
+}
+
+int fc_ref_allreduce_sim_sym(const uint16_t *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                             int group, int bits_rs, int bits_ag, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits_rs) || !check_shape(tokens, hidden, group, bits_ag)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    const int64_t m = tokens * hidden, ng = m / group;
+    const int64_t cb_rs = m * bits_rs / 8, cb_ag = m * bits_ag / 8;
+    uint8_t *c1 = (uint8_t *)malloc((size_t)(cb_rs * n_src));
+    float *s1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    uint8_t *c2 = (uint8_t *)malloc((size_t)cb_ag);
+    float *s2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    int rc = (c1 && s1 && c2 && s2) ? FC_REF_OK : FC_REF_NO_MEM;
+    for (int j = 0; rc == FC_REF_OK && j < n_src; ++j)
+        rc = fc_ref_quantize_sym(x_f16 + (int64_t)j * m, tokens, hidden, group, bits_rs,
+                                 c1 + (int64_t)j * cb_rs, s1 + (int64_t)j * ng);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequant_reduce_requant_sym(c1, cb_rs, s1, ng, n_src, tokens, hidden, group,
+                                               bits_rs, bits_ag, c2, s2);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequantize_sym(c2, s2, tokens, hidden, group, bits_ag, y_f16);
+    free(c1); free(s1); free(c2); free(s2);
     return rc;
 }
