@@ -36,20 +36,21 @@ HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
 
 
 def fused_bytes(w) -> int:
-    """Algorithmic bytes of one fused launch: N x (codes + scale + zero-point) in,
-    codes + scale + zero-point out (fp32 meta, 8 bytes per group)."""
+    """Algorithmic bytes of one fused launch: N x (codes + meta) in, codes + meta out; meta is an
+    fp32 scale and zero-point per group (8 bytes), or the scale alone (4) for the symmetric quantizer."""
     m = w.elements
-    return w.n_src * (m * w.bits_in // 8 + 8 * m // w.group) + m * w.bits_out // 8 + 8 * m // w.group
+    mb = w.meta_bytes_per_group
+    return w.n_src * (m * w.bits_in // 8 + mb * m // w.group) + m * w.bits_out // 8 + mb * m // w.group
 
 
 def quantize_bytes(w) -> int:
     m = w.elements
-    return 2 * m + m * w.bits_in // 8 + 8 * m // w.group
+    return 2 * m + m * w.bits_in // 8 + w.meta_bytes_per_group * m // w.group
 
 
 def dequantize_bytes(w) -> int:
     m = w.elements
-    return m * w.bits_out // 8 + 8 * m // w.group + 2 * m
+    return m * w.bits_out // 8 + w.meta_bytes_per_group * m // w.group + 2 * m
 
 
 def load_traffic(name):
@@ -76,13 +77,18 @@ def cpu_baseline(w, x_host, budget_s=20.0):
     if est * 3 > budget_s:
         rows = max(16, int(w.tokens * budget_s / (est * 3)))
     xs = x_host[:, :rows]
-    parts = [oracle.quantize(xs[j], w.group, w.bits_in) for j in range(w.n_src)]
+    sym = w.quantizer == "sym"
+    parts = [(oracle.quantize_sym if sym else oracle.quantize)(xs[j], w.group, w.bits_in)
+             for j in range(w.n_src)]
     c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
-    z = np.stack([p[2] for p in parts])
+    z = None if sym else np.stack([p[2] for p in parts])
     best = None
     for _ in range(2):
         t0 = time.perf_counter()
-        oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
+        if sym:
+            oracle.dequant_reduce_requant_sym(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
+        else:
+            oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
     frac = rows / w.tokens
@@ -137,16 +143,27 @@ def main():
     Z2 = [torch.empty_like(S2[0]) for _ in range(B)]
     Y = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in range(B)]
 
+    sym = w.quantizer == "sym"
+
     def stage_quantize(k):
         for j in range(N):
-            fc.quantize(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j], Z1[k][j]))
+            if sym:
+                fc.quantize_sym(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j]))
+            else:
+                fc.quantize(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j], Z1[k][j]))
 
     def stage_fused(k):
-        fc.dequant_reduce_requant(C1[k], S1[k], Z1[k], H, g, w.bits_in, w.bits_out,
-                                  out=(C2[k], S2[k], Z2[k]))
+        if sym:
+            fc.dequant_reduce_requant_sym(C1[k], S1[k], H, g, w.bits_in, w.bits_out, out=(C2[k], S2[k]))
+        else:
+            fc.dequant_reduce_requant(C1[k], S1[k], Z1[k], H, g, w.bits_in, w.bits_out,
+                                      out=(C2[k], S2[k], Z2[k]))
 
     def stage_dequantize(k):
-        fc.dequantize(C2[k], S2[k], Z2[k], H, g, w.bits_out, out=Y[k])
+        if sym:
+            fc.dequantize_sym(C2[k], S2[k], H, g, w.bits_out, out=Y[k])
+        else:
+            fc.dequantize(C2[k], S2[k], Z2[k], H, g, w.bits_out, out=Y[k])
 
     ev = {name: [] for name in ("q", "f", "d")}
 
@@ -209,8 +226,9 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "%s: N=%d partial fp16 tensors of %d tokens x %d hidden, N(0,1) with %g%% outlier "
-                        "channels x%g, INT%d->INT%d asymmetric, group %d"
-                        % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain, w.bits_in, w.bits_out, g),
+                        "channels x%g, INT%d->INT%d %s, group %d"
+                        % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain, w.bits_in, w.bits_out,
+                           "symmetric" if sym else "asymmetric", g),
             "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
             "volumes_per_step": B,
             "stage_order": "volume-major (dependent)" if a.dependent else "stage-major over the batch",
@@ -225,7 +243,7 @@ def main():
             "whole_path_GBps": round(B * vol_bytes / (wall / a.steps) / 1e9, 1),
         },
         "roofline": {
-            "kernel": "k_dequant_reduce_requant<%d,%d,%d>" % (w.bits_in, w.bits_out, N),
+            "kernel": "k_dequant_reduce_requant%s<%d,%d,%d>" % ("_sym" if sym else "", w.bits_in, w.bits_out, N),
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,

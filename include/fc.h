@@ -136,6 +136,37 @@ FC_API int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_
 FC_API size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
                                                int bits_rs, int bits_ag);
 
+/*
+ * Symmetric variant (Appendix "Quantization Fundamentals", Eq. 3-4; the paper's
+ * INT8_Sym / INT4_Sym ablation rows).  Same layouts and rules as above except:
+ * there is no zero-point array, and codes are SIGNED, stored in two's
+ * complement (8 bit: one int8 per byte; 4 bit: two per byte, element 2k in bits
+ * 0-3).  Results are bit-identical to evaluating, for every group,
+ *     s   = max|x| / (2^(bits-1) - 1)           one IEEE divide
+ *     if !(s >= FLT_MIN): s = 1                  (all-zero group)
+ *     inv = 1 / s                                 one IEEE divide
+ *     q   = clamp(rint(x * inv), -2^(bits-1), 2^(bits-1) - 1)
+ * Dequantize: x^ = q * s.  ReduceSum: acc = +0; acc = fma(q_j, s_j, acc), j = 0..N-1.
+ */
+FC_API int fc_quantize_sym(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                           void *codes, float *scales, void *hip_stream);
+
+FC_API int fc_dequant_reduce_requant_sym(const void *codes_in, int64_t codes_src_stride_bytes,
+                                         const float *scales_in, int64_t meta_src_stride_elems,
+                                         int n_src, int64_t tokens, int64_t hidden, int group,
+                                         int bits_in, int bits_out,
+                                         void *codes_out, float *scales_out, void *hip_stream);
+
+FC_API int fc_dequantize_sym(const void *codes, const float *scales,
+                             int64_t tokens, int64_t hidden, int group, int bits,
+                             void *y_f16, void *hip_stream);
+
+/* Algorithm 1 end to end with the symmetric quantizer; workspace as for fc_allreduce_sim
+   (fc_allreduce_sim_workspace_bytes gives a sufficient size). */
+FC_API int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                                int group, int bits_rs, int bits_ag, void *y_f16,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);
 

@@ -67,31 +67,26 @@ SimLayout sim_layout(int n_src, int64_t n_elems, int group, int bits_rs, int bit
     return L;
 }
 
-}  // namespace
-
-extern "C" {
-
-int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
-                void *codes, float *scales, float *zeros, void *hip_stream)
+// The asymmetric and symmetric entry points share these; `sym` drops the
+// zero-point arrays (passed as nullptr to the launchers).
+int quantize_impl(bool sym, const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                  void *codes, float *scales, float *zeros, void *hip_stream)
 {
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits, &n);
     if (rc != FC_OK) return rc;
     if (n == 0) return FC_OK;
-    if (!x_f16 || !codes || !scales || !zeros) return FC_ERR_NULL;
-    if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros))
+    if (!x_f16 || !codes || !scales || (!sym && !zeros)) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || (!sym && !aligned16(zeros)))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_quantize(bits, x_f16, n, group, codes, scales, zeros,
+    return hip_result(fc::launch_quantize(bits, x_f16, n, group, codes, scales, sym ? nullptr : zeros,
                                           static_cast<hipStream_t>(hip_stream)));
 }
 
-int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
-                              const float *scales_in, const float *zeros_in,
-                              int64_t meta_src_stride_elems,
-                              int n_src, int64_t tokens, int64_t hidden, int group,
-                              int bits_in, int bits_out,
-                              void *codes_out, float *scales_out, float *zeros_out,
-                              void *hip_stream)
+int fused_impl(bool sym, const void *codes_in, int64_t codes_src_stride_bytes,
+               const float *scales_in, const float *zeros_in, int64_t meta_src_stride_elems,
+               int n_src, int64_t tokens, int64_t hidden, int group, int bits_in, int bits_out,
+               void *codes_out, float *scales_out, float *zeros_out, void *hip_stream)
 {
     int64_t n = 0;
     int rc = check_shape(tokens, hidden, group, bits_in, &n);
@@ -99,7 +94,7 @@ int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_byt
     if (bits_out != 4 && bits_out != 8) return FC_ERR_BITS;
     if (n_src < 1 || n_src > FC_MAX_SRC) return FC_ERR_SHAPE;
     if (n == 0) return FC_OK;
-    if (!codes_in || !scales_in || !zeros_in || !codes_out || !scales_out || !zeros_out)
+    if (!codes_in || !scales_in || !codes_out || !scales_out || (!sym && (!zeros_in || !zeros_out)))
         return FC_ERR_NULL;
     if (n_src > 1) {
         if (codes_src_stride_bytes < n * bits_in / 8 || meta_src_stride_elems < n / group)
@@ -109,22 +104,22 @@ int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_byt
         codes_src_stride_bytes = 0;
         meta_src_stride_elems = 0;
     }
-    if (!aligned16(codes_in) || !aligned16(scales_in) || !aligned16(zeros_in) ||
-        !aligned16(codes_out) || !aligned16(scales_out) || !aligned16(zeros_out))
+    if (!aligned16(codes_in) || !aligned16(scales_in) || !aligned16(codes_out) || !aligned16(scales_out) ||
+        (!sym && (!aligned16(zeros_in) || !aligned16(zeros_out))))
         return FC_ERR_ALIGN;
 
     fc::FusedArgs a;
     a.codes_in = codes_in;
     a.codes_stride = codes_src_stride_bytes;
     a.scales_in = scales_in;
-    a.zeros_in = zeros_in;
+    a.zeros_in = sym ? nullptr : zeros_in;
     a.meta_stride = meta_src_stride_elems;
     a.n_src = n_src;
     a.n_elems = n;
     a.group = group;
     a.codes_out = codes_out;
     a.scales_out = scales_out;
-    a.zeros_out = zeros_out;
+    a.zeros_out = sym ? nullptr : zeros_out;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (bits_in == 4)
@@ -134,34 +129,23 @@ int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_byt
     return hip_result(e);
 }
 
-int fc_dequantize(const void *codes, const float *scales, const float *zeros,
-                  int64_t tokens, int64_t hidden, int group, int bits,
-                  void *y_f16, void *hip_stream)
+int dequantize_impl(bool sym, const void *codes, const float *scales, const float *zeros,
+                    int64_t tokens, int64_t hidden, int group, int bits, void *y_f16, void *hip_stream)
 {
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits, &n);
     if (rc != FC_OK) return rc;
     if (n == 0) return FC_OK;
-    if (!codes || !scales || !zeros || !y_f16) return FC_ERR_NULL;
-    if (!aligned16(codes) || !aligned16(scales) || !aligned16(zeros) || !aligned16(y_f16))
+    if (!codes || !scales || !y_f16 || (!sym && !zeros)) return FC_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(y_f16) || (!sym && !aligned16(zeros)))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_dequantize(bits, codes, scales, zeros, n, group, y_f16,
+    return hip_result(fc::launch_dequantize(bits, codes, scales, sym ? nullptr : zeros, n, group, y_f16,
                                             static_cast<hipStream_t>(hip_stream)));
 }
 
-size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
-                                        int bits_rs, int bits_ag)
-{
-    int64_t n = 0;
-    if (check_shape(tokens, hidden, group, bits_rs, &n) != FC_OK) return 0;
-    if (bits_ag != 4 && bits_ag != 8) return 0;
-    if (n_src < 1 || n_src > FC_MAX_SRC) return 0;
-    return sim_layout(n_src, n, group, bits_rs, bits_ag).total;
-}
-
-int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
-                     int group, int bits_rs, int bits_ag, void *y_f16,
-                     void *workspace, size_t workspace_bytes, void *hip_stream)
+int allreduce_sim_impl(bool sym, const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                       int group, int bits_rs, int bits_ag, void *y_f16,
+                       void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits_rs, &n);
@@ -178,24 +162,103 @@ int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidde
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
     for (int j = 0; j < n_src; ++j) {
-        const int q = fc_quantize(x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
-                                  ws + L.off_codes1 + (size_t)j * L.codes_rs,
-                                  reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
-                                  reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta),
-                                  hip_stream);
+        const int q = quantize_impl(sym, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
+                                    ws + L.off_codes1 + (size_t)j * L.codes_rs,
+                                    reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
+                                    reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta),
+                                    hip_stream);
         if (q != FC_OK) return q;
     }
-    const int f = fc_dequant_reduce_requant(
-        ws + L.off_codes1, (int64_t)L.codes_rs,
-        reinterpret_cast<const float *>(ws + L.off_scales1),
-        reinterpret_cast<const float *>(ws + L.off_zeros1), (int64_t)(L.meta / sizeof(float)),
-        n_src, tokens, hidden, group, bits_rs, bits_ag, ws + L.off_codes2,
-        reinterpret_cast<float *>(ws + L.off_scales2), reinterpret_cast<float *>(ws + L.off_zeros2),
-        hip_stream);
+    const int f = fused_impl(sym, ws + L.off_codes1, (int64_t)L.codes_rs,
+                             reinterpret_cast<const float *>(ws + L.off_scales1),
+                             reinterpret_cast<const float *>(ws + L.off_zeros1),
+                             (int64_t)(L.meta / sizeof(float)), n_src, tokens, hidden, group, bits_rs,
+                             bits_ag, ws + L.off_codes2, reinterpret_cast<float *>(ws + L.off_scales2),
+                             reinterpret_cast<float *>(ws + L.off_zeros2), hip_stream);
     if (f != FC_OK) return f;
-    return fc_dequantize(ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
-                         reinterpret_cast<const float *>(ws + L.off_zeros2), tokens, hidden, group,
-                         bits_ag, y_f16, hip_stream);
+    return dequantize_impl(sym, ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
+                           reinterpret_cast<const float *>(ws + L.off_zeros2), tokens, hidden, group,
+                           bits_ag, y_f16, hip_stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                void *codes, float *scales, float *zeros, void *hip_stream)
+{
+    return quantize_impl(false, x_f16, tokens, hidden, group, bits, codes, scales, zeros, hip_stream);
+}
+
+int fc_quantize_sym(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                    void *codes, float *scales, void *hip_stream)
+{
+    return quantize_impl(true, x_f16, tokens, hidden, group, bits, codes, scales, nullptr, hip_stream);
+}
+
+int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
+                              const float *scales_in, const float *zeros_in,
+                              int64_t meta_src_stride_elems,
+                              int n_src, int64_t tokens, int64_t hidden, int group,
+                              int bits_in, int bits_out,
+                              void *codes_out, float *scales_out, float *zeros_out,
+                              void *hip_stream)
+{
+    return fused_impl(false, codes_in, codes_src_stride_bytes, scales_in, zeros_in, meta_src_stride_elems,
+                      n_src, tokens, hidden, group, bits_in, bits_out, codes_out, scales_out, zeros_out,
+                      hip_stream);
+}
+
+int fc_dequant_reduce_requant_sym(const void *codes_in, int64_t codes_src_stride_bytes,
+                                  const float *scales_in, int64_t meta_src_stride_elems,
+                                  int n_src, int64_t tokens, int64_t hidden, int group,
+                                  int bits_in, int bits_out,
+                                  void *codes_out, float *scales_out, void *hip_stream)
+{
+    return fused_impl(true, codes_in, codes_src_stride_bytes, scales_in, nullptr, meta_src_stride_elems,
+                      n_src, tokens, hidden, group, bits_in, bits_out, codes_out, scales_out, nullptr,
+                      hip_stream);
+}
+
+int fc_dequantize(const void *codes, const float *scales, const float *zeros,
+                  int64_t tokens, int64_t hidden, int group, int bits,
+                  void *y_f16, void *hip_stream)
+{
+    return dequantize_impl(false, codes, scales, zeros, tokens, hidden, group, bits, y_f16, hip_stream);
+}
+
+int fc_dequantize_sym(const void *codes, const float *scales,
+                      int64_t tokens, int64_t hidden, int group, int bits,
+                      void *y_f16, void *hip_stream)
+{
+    return dequantize_impl(true, codes, scales, nullptr, tokens, hidden, group, bits, y_f16, hip_stream);
+}
+
+size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
+                                        int bits_rs, int bits_ag)
+{
+    int64_t n = 0;
+    if (check_shape(tokens, hidden, group, bits_rs, &n) != FC_OK) return 0;
+    if (bits_ag != 4 && bits_ag != 8) return 0;
+    if (n_src < 1 || n_src > FC_MAX_SRC) return 0;
+    return sim_layout(n_src, n, group, bits_rs, bits_ag).total;
+}
+
+int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                     int group, int bits_rs, int bits_ag, void *y_f16,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return allreduce_sim_impl(false, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+                              workspace, workspace_bytes, hip_stream);
+}
+
+int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                         int group, int bits_rs, int bits_ag, void *y_f16,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return allreduce_sim_impl(true, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+                              workspace, workspace_bytes, hip_stream);
 }
 
 const char *fc_strerror(int code)

@@ -8,8 +8,12 @@ template <int BITS, int LPG>
 static void launch_q(dim3 grid, hipStream_t stream, const uint16_t *x, int64_t n_elems, int lpg,
                      int group_shift, uint8_t *c, float *scales, float *zeros)
 {
-    k_quantize<BITS, LPG><<<grid, dim3(kBlockThreads), 0, stream>>>(x, n_elems, lpg, group_shift, c,
-                                                                   scales, zeros);
+    if (zeros)
+        k_quantize<BITS, LPG, false><<<grid, dim3(kBlockThreads), 0, stream>>>(x, n_elems, lpg, group_shift,
+                                                                              c, scales, zeros);
+    else
+        k_quantize<BITS, LPG, true><<<grid, dim3(kBlockThreads), 0, stream>>>(x, n_elems, lpg, group_shift,
+                                                                             c, scales, nullptr);
 }
 
 template <int BITS>
@@ -46,15 +50,16 @@ hipError_t launch_dequantize(int bits, const void *codes, const float *scales, c
     const uint8_t *c = static_cast<const uint8_t *>(codes);
     uint16_t *y = static_cast<uint16_t *>(y_f16);
     const int sh = log2_int(group);
-    if (bits == 4) {
-        const int64_t tile = block_elems(4);
-        k_dequantize<4><<<dim3((unsigned)((n_elems + tile - 1) / tile)), dim3(kBlockThreads), 0, stream>>>(
-            c, scales, zeros, n_elems, sh, y);
-    } else {
-        const int64_t tile = block_elems(8);
-        k_dequantize<8><<<dim3((unsigned)((n_elems + tile - 1) / tile)), dim3(kBlockThreads), 0, stream>>>(
-            c, scales, zeros, n_elems, sh, y);
-    }
+    const int64_t tile = block_elems(bits);
+    const dim3 grid((unsigned)((n_elems + tile - 1) / tile)), block(kBlockThreads);
+    if (bits == 4 && zeros)
+        k_dequantize<4, false><<<grid, block, 0, stream>>>(c, scales, zeros, n_elems, sh, y);
+    else if (bits == 4)
+        k_dequantize<4, true><<<grid, block, 0, stream>>>(c, scales, nullptr, n_elems, sh, y);
+    else if (zeros)
+        k_dequantize<8, false><<<grid, block, 0, stream>>>(c, scales, zeros, n_elems, sh, y);
+    else
+        k_dequantize<8, true><<<grid, block, 0, stream>>>(c, scales, nullptr, n_elems, sh, y);
     return hipGetLastError();
 }
 

@@ -331,6 +331,106 @@ __device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
     }
 }
 
+struct ZeroConst {
+    h2 c1024;   // (1024 + z, 1024 + z)
+    h2 c64;     // (64 + z, 64 + z)
+};
+
+// ---------------------------------------------------------------------------
+// Symmetric variant (paper Appendix, Eq. 3-4): s = max|X| / (2^(n-1) - 1),
+// q = clamp(rint(X * (1/s)), -2^(n-1), 2^(n-1) - 1), signed codes stored in two's
+// complement, no zero-point.
+// ---------------------------------------------------------------------------
+template <int LPG>
+__device__ __forceinline__ float group_max(float m, int lpg_rt)
+{
+    const int lpg = LPG > 0 ? LPG : lpg_rt;
+    if (lpg >= 2) m = fmaxf(m, dpp_read<kDppQuadXor1>(m));
+    if (lpg >= 4) m = fmaxf(m, dpp_read<kDppQuadXor2>(m));
+    if (lpg >= 8) m = fmaxf(m, dpp_read<kDppRowHalfMirror>(m));
+    if (lpg >= 16) m = fmaxf(m, dpp_read<kDppRowMirror>(m));
+    if (lpg >= 32) m = fmaxf(m, __shfl_xor(m, 16));
+    if (lpg >= 64) m = fmaxf(m, __shfl_xor(m, 32));
+    return m;
+}
+
+// Eq. 3 with the same exhaustively checked division sequences as group_params
+// (r/7 and r/127 match the IEEE quotient for every positive fp32 as well).
+template <int BITS>
+__device__ __forceinline__ void group_params_sym(float amax, float &s, float &inv)
+{
+    constexpr float qm = (float)((1 << (BITS - 1)) - 1);
+    constexpr float c = 1.0f / qm;
+    const float q0 = amax * c;
+    const float e = fmaf(-qm, q0, amax);
+    s = fmaf(e, c, q0);                    // == amax / qm
+    if (!(s >= FLT_MIN)) s = 1.0f;         // all-zero (or vanishing) group
+    if (__builtin_amdgcn_ballot_w64(!(s <= 0x1p100f)) == 0) {
+        const float y0 = __builtin_amdgcn_rcpf(s);
+        const float e1 = fmaf(-s, y0, 1.0f);
+        inv = fmaf(e1, y0, y0);            // == 1 / s
+    } else {
+        inv = 1.0f / s;
+    }
+}
+
+// Symmetric FinegrainedQuantize of the lane's EPL values.  |x| <= amax makes
+// |x*inv| <= amax*inv = qm*(1 + O(2^-22)), so |rint(x*inv)| <= qm and neither
+// clamp of Eq. 4 can act.  Digits are merged with the exact fp32 Horner steps
+// of the asymmetric path after a bias of 2^(n-1) per digit, and the bias is
+// removed again by flipping each digit's top bit (offset binary -> two's
+// complement).
+template <int BITS, int EPL, int LPG>
+__device__ __forceinline__ void quantize_lane_sym(const float (&v)[EPL], int lpg_rt,
+                                                  u32 (&word)[EPL * BITS / 32], float &s)
+{
+    float amax = fabsf(v[0]);
+#pragma unroll
+    for (int i = 1; i < EPL; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    amax = group_max<LPG>(amax, lpg_rt);
+    float inv;
+    group_params_sym<BITS>(amax, s, inv);
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int w = 0; w < EPL / 8; ++w) {
+            float t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = rintf(v[8 * w + i] * inv);
+            const float lo = fmaf(fmaf(fmaf(t[3], 16.0f, t[2]), 16.0f, t[1]), 16.0f, t[0]) + 34952.0f;
+            const float hi = fmaf(fmaf(fmaf(t[7], 16.0f, t[6]), 16.0f, t[5]), 16.0f, t[4]) + 34952.0f;
+            word[w] = ((u32)lo | ((u32)hi << 16)) ^ 0x88888888u;      // 34952 = 8 * 0x1111
+        }
+    } else {
+#pragma unroll
+        for (int w = 0; w < EPL / 4; ++w) {
+            float t[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] = rintf(v[4 * w + i] * inv);
+            const float lo = fmaf(t[1], 256.0f, t[0]) + 32896.0f;     // 32896 = 128 * 0x0101
+            const float hi = fmaf(t[3], 256.0f, t[2]) + 32896.0f;
+            word[w] = ((u32)lo | ((u32)hi << 16)) ^ 0x80808080u;
+        }
+    }
+}
+
+// signed codes -> offset binary (q + 2^(n-1)) and the matching "zero-point"
+template <int BITS>
+__device__ __forceinline__ u32 to_offset_binary(u32 w)
+{
+    return w ^ (BITS == 4 ? 0x88888888u : 0x80808080u);
+}
+
+template <int BITS>
+__device__ __forceinline__ ZeroConst sym_zero_const()
+{
+    constexpr float bias = (float)(1 << (BITS - 1));
+    ZeroConst z;
+    const _Float16 a = (_Float16)(1024.0f + bias), b = (_Float16)(64.0f + bias);
+    z.c1024 = h2{a, a};
+    z.c64 = h2{b, b};
+    return z;
+}
+
 // Store the lane's code words.  `r` addresses the workgroup's tile of the code
 // array.  8 or 16 bytes per lane go out directly (coalesced); 32 bytes per lane
 // are first laid out in the wavefront's LDS scratch `img` (2 KB) as they will
@@ -375,11 +475,6 @@ __device__ __forceinline__ void store_f32(rsrc_t r, u32 byte_off, float v)
 // widening to fp32 is exact, so d is bit-identical to the fp32 (float)q - z.
 // General path: convert and subtract in fp32.
 // ---------------------------------------------------------------------------
-struct ZeroConst {
-    h2 c1024;   // (1024 + z, 1024 + z)
-    h2 c64;     // (64 + z, 64 + z)
-};
-
 __device__ __forceinline__ bool zero_is_fast(float zf)
 {
     return (zf == rintf(zf)) && (zf >= -1700.0f) && (zf <= 1000.0f);
@@ -528,7 +623,8 @@ __device__ __forceinline__ void accumulate_general(const u32 (&w)[4], float s, f
 // One tile of 256*EPL elements per workgroup.  The wavefront's 64*EPL*2 input
 // bytes are fetched as coalesced 1 KB pieces straight into LDS (an image of
 // global memory) and each lane then reads its EPL contiguous values from there.
-template <int BITS, int LPG>
+// SYM selects the symmetric quantizer (Eq. 3-4; `zeros` is then unused).
+template <int BITS, int LPG, bool SYM>
 __global__ FC_KERNEL_ATTRS void k_quantize(
     const uint16_t *__restrict__ x, int64_t n_elems, int lpg, int group_shift,
     uint8_t *__restrict__ codes, float *__restrict__ scales, float *__restrict__ zeros)
@@ -544,7 +640,7 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
     const rsrc_t rx = make_rsrc(x + e_tile, (n_elems - e_tile) * 2);
     const rsrc_t rc = make_rsrc(codes + e_tile * BITS / 8, (n_elems - e_tile) * BITS / 8);
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
-    const rsrc_t rz = make_rsrc(zeros + g_tile, (n_groups - g_tile) * 4);
+    const rsrc_t rz = make_rsrc(SYM ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
 
 #pragma unroll
     for (int k = 0; k < kPieces; ++k)
@@ -565,14 +661,17 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
     }
 
     u32 word[EPL * BITS / 32];
-    float s, zf;
-    quantize_lane<BITS, EPL, LPG>(v, lpg, word, s, zf);
+    float s, zf = 0.0f;
+    if constexpr (SYM)
+        quantize_lane_sym<BITS, EPL, LPG>(v, lpg, word, s);
+    else
+        quantize_lane<BITS, EPL, LPG>(v, lpg, word, s, zf);
     store_codes<16>(word, rc, wave, lane, nullptr);
     const int lpg_v = LPG > 0 ? LPG : lpg;
     if ((tid & (lpg_v - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
         store_f32(rs, gi * 4, s);
-        store_f32(rz, gi * 4, zf);
+        if constexpr (!SYM) store_f32(rz, gi * 4, zf);
     }
 }
 
@@ -706,10 +805,75 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
     }
 }
 
+// Symmetric version of the fused kernel (Eq. 3-4 on both sides): same staging
+// and tiling; the signed codes are flipped to offset binary with one XOR per
+// word and then take the fast path above with the constant "zero-point"
+// 2^(n-1), so there is nothing to check or tabulate: each lane reads its
+// group's scale of every source directly.
+template <int BITS_IN, int BITS_OUT, int NSRC, int LPG>
+__global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
+    const uint8_t *__restrict__ codes_in, int64_t codes_stride,
+    const float *__restrict__ scales_in, int64_t meta_stride,
+    int64_t n_elems, int lpg, int group_shift,
+    uint8_t *__restrict__ codes_out, float *__restrict__ scales_out)
+{
+    constexpr int EPL = lane_elems(BITS_IN);
+    constexpr int kTileElems = kBlockThreads * EPL;
+    constexpr int kOutBytes = EPL * BITS_OUT / 8;
+    __shared__ __attribute__((aligned(16))) uint8_t landing[kBlockWaves][NSRC][1024];
+    __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kBlockWaves : 1]
+                                                            [kOutBytes == 32 ? 2048 : 16];
+
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const int64_t n_groups = n_elems >> group_shift;
+    const int lpg_v = LPG > 0 ? LPG : lpg;
+    const u32 tile = xcd_tile();
+    const int64_t e_tile = (int64_t)tile * kTileElems;
+    const int64_t g_tile = e_tile >> group_shift;
+    const u32 gi = (tid * EPL) >> group_shift;
+
+    int64_t g_lane = g_tile + gi;
+    g_lane = g_lane < n_groups ? g_lane : n_groups - 1;       // ragged tail: stay inside the array
+    float sc[NSRC];
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) sc[j] = scales_in[(int64_t)j * meta_stride + g_lane];
+    issue_order_fence();
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) {
+        const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
+                                    (n_elems - e_tile) * BITS_IN / 8);
+        dma_piece(rc, tid * 16, &landing[wave][j][0]);
+    }
+    issue_order_fence();
+
+    const ZeroConst zc = sym_zero_const<BITS_IN>();
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) {
+        wait_vmem_outstanding(NSRC - 1 - j);
+        u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+        lds_read_complete(a);
+        const u32 w[4] = {to_offset_binary<BITS_IN>(a[0]), to_offset_binary<BITS_IN>(a[1]),
+                          to_offset_binary<BITS_IN>(a[2]), to_offset_binary<BITS_IN>(a[3])};
+        accumulate_fast<BITS_IN>(w, sc[j], zc, acc);
+        pin_values(acc);
+    }
+
+    u32 word[EPL * BITS_OUT / 32];
+    float s;
+    quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, lpg, word, s);
+    const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
+    const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
+    store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
+    if ((tid & (lpg_v - 1)) == 0) store_f32(rs, gi * 4, s);
+}
+
 // Dequantize to binary16 (Algorithm 1, last step): y = half_rne((q - z) * s).
 // One tile of 256*EPL elements per workgroup; the EPL halves of a lane are laid
 // out in the wavefront's LDS image and leave as coalesced 1 KB pieces.
-template <int BITS>
+template <int BITS, bool SYM>
 __global__ FC_KERNEL_ATTRS void k_dequantize(
     const uint8_t *__restrict__ codes, const float *__restrict__ scales,
     const float *__restrict__ zeros, int64_t n_elems, int group_shift, uint16_t *__restrict__ y)
@@ -725,20 +889,26 @@ __global__ FC_KERNEL_ATTRS void k_dequantize(
     const u32 gi = (tid * EPL) >> group_shift;
     const rsrc_t rc = make_rsrc(codes + e_tile * BITS / 8, (n_elems - e_tile) * BITS / 8);
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
-    const rsrc_t rz = make_rsrc(zeros + g_tile, (n_groups - g_tile) * 4);
+    const rsrc_t rz = make_rsrc(SYM ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t ry = make_rsrc(y + e_tile, (n_elems - e_tile) * 2);
 
     const float s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
-    const float zf = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rz, gi * 4, 0, 0));
     const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamPolicy);
-    const u32 w[4] = {a[0], a[1], a[2], a[3]};
 
     float d[EPL];
-    const bool wave_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0;
-    if (wave_fast)
-        codes_minus_zero_fast<BITS>(w, unpack_zero_const(pack_zero_const(zf)), d);
-    else
-        codes_minus_zero_general<BITS>(w, zf, d);
+    if constexpr (SYM) {
+        const u32 w[4] = {to_offset_binary<BITS>(a[0]), to_offset_binary<BITS>(a[1]),
+                          to_offset_binary<BITS>(a[2]), to_offset_binary<BITS>(a[3])};
+        codes_minus_zero_fast<BITS>(w, sym_zero_const<BITS>(), d);
+    } else {
+        const float zf = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rz, gi * 4, 0, 0));
+        const u32 w[4] = {a[0], a[1], a[2], a[3]};
+        const bool wave_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0;
+        if (wave_fast)
+            codes_minus_zero_fast<BITS>(w, unpack_zero_const(pack_zero_const(zf)), d);
+        else
+            codes_minus_zero_general<BITS>(w, zf, d);
+    }
 
     u32x4 *mine = reinterpret_cast<u32x4 *>(&img[wave][lane * (EPL * 2)]);
 #pragma unroll

@@ -18,6 +18,14 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 {
     const int64_t tile = block_elems(FC_BITS_IN);
     const int64_t blocks = (a.n_elems + tile - 1) / tile;
+    if (a.zeros_in == nullptr) {
+        k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
+            <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+                static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
+                a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                static_cast<uint8_t *>(a.codes_out), a.scales_out);
+        return hipGetLastError();
+    }
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
         <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,

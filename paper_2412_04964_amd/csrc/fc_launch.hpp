@@ -8,13 +8,15 @@
 namespace fc {
 
 // n_elems = tokens*hidden (a multiple of `group`, which is a power of two in
-// [32, 1024]).  All pointers are device pointers.
+// [32, 1024]).  All pointers are device pointers.  zeros == nullptr selects the
+// symmetric quantizer (scales only).
 hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int group,
                            void *codes, float *scales, float *zeros, hipStream_t stream);
 
 hipError_t launch_dequantize(int bits, const void *codes, const float *scales, const float *zeros,
                              int64_t n_elems, int group, void *y_f16, hipStream_t stream);
 
+// zeros_in == nullptr (and zeros_out == nullptr) selects the symmetric quantizer
 struct FusedArgs {
     const void *codes_in;
     int64_t codes_stride;

@@ -30,14 +30,20 @@ class Workload:
     outlier_frac: float = 0.01
     outlier_gain: float = 20.0
     seed: int = 0
+    quantizer: str = "asym"   # "asym": Eq. 1-2 (scale + zero-point), "sym": Eq. 3-4 (scale only)
 
     @property
     def elements(self) -> int:
         return self.tokens * self.hidden
 
+    @property
+    def meta_bytes_per_group(self) -> int:
+        return 8 if self.quantizer == "asym" else 4
+
 
 # The five configurations the benchmark contract names, plus the paper's mixed-precision
-# "INT6" setting (4 bit before the reduce, 8 bit before the gather; Section 3.2.3) at the headline shape.
+# "INT6" setting (4 bit before the reduce, 8 bit before the gather; Section 3.2.3) at the headline shape,
+# and the symmetric quantizer of the paper's ablation (Table 6) at the two prefill shapes.
 WORKLOADS = {
     "tiny": Workload("tiny", 2, 16, 4096, 8, 8, 128, outlier_frac=0.0),
     "llama3_8b_prefill": Workload("llama3_8b_prefill", 4, 8192, 4096, 8, 8, 128),
@@ -45,6 +51,8 @@ WORKLOADS = {
     "wide_fanin": Workload("wide_fanin", 8, 8192, 8192, 4, 4, 64),
     "decode": Workload("decode", 8, 8, 8192, 8, 8, 128),
     "llama3_70b_prefill_int6": Workload("llama3_70b_prefill_int6", 4, 8192, 8192, 4, 8, 128),
+    "llama3_70b_prefill_sym": Workload("llama3_70b_prefill_sym", 4, 8192, 8192, 4, 4, 128, quantizer="sym"),
+    "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
 }
 
 
