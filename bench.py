@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0,
                     help="independent volumes per step (0 = enough for >= 4 GiB of traffic per step)")
     ap.add_argument("--dependent", action="store_true", help="run the stages of one volume back to back")
+    ap.add_argument("--group", type=int, default=0,
+                    help="override the workload's group size (granularity sweep; 0 = as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
 
@@ -126,6 +128,9 @@ def main():
     fc.lib()
 
     w = synth_inputs.WORKLOADS[a.workload]
+    if a.group:
+        import dataclasses
+        w = dataclasses.replace(w, name="%s_g%d" % (w.name, a.group), group=a.group)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     T, H, N, g = w.tokens, w.hidden, w.n_src, w.group

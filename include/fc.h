@@ -39,7 +39,7 @@
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No call synchronizes.  The device that is current
  *     on the calling thread must own the buffers and the stream.
- *   - bits in {4, 8};  group in {32, 64, 128, 256, 512, 1024};
+ *   - bits in {4, 8};  group a power of two in [32, 16384] (group == hidden: one group per token);
  *     hidden % group == 0;  tokens >= 0 (0 is a no-op returning FC_OK);
  *     tokens*hidden <= 2^36;  1 <= n_src <= FC_MAX_SRC.
  *   - Inputs must be finite.  NaN / Inf inputs give unspecified codes.

@@ -17,6 +17,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int log2_exact(int v)
 {
+    if (v <= 0 || v > (1 << 20)) return -1;
     int s = 0;
     while ((1 << s) < v) ++s;
     return ((1 << s) == v) ? s : -1;
@@ -27,7 +28,7 @@ int check_shape(int64_t tokens, int64_t hidden, int group, int bits, int64_t *n_
 {
     if (bits != 4 && bits != 8) return FC_ERR_BITS;
     const int sh = log2_exact(group);
-    if (sh < 5 || sh > 10) return FC_ERR_GROUP;            // 32 .. 1024
+    if (sh < 5 || sh > 14) return FC_ERR_GROUP;            // 32 .. 16384
     if (tokens < 0 || hidden <= 0) return FC_ERR_SHAPE;
     if (hidden % group != 0) return FC_ERR_GROUP;
     if (hidden > kMaxElems || (tokens > 0 && tokens > kMaxElems / hidden)) return FC_ERR_SHAPE;
@@ -122,7 +123,9 @@ int fused_impl(bool sym, const void *codes_in, int64_t codes_src_stride_bytes,
     a.zeros_out = sym ? nullptr : zeros_out;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
-    if (bits_in == 4)
+    if (fc::exceeds_tile(bits_in, group))
+        e = fc::launch_fused_wide(bits_in, bits_out, a, st);
+    else if (bits_in == 4)
         e = (bits_out == 4) ? fc::launch_fused_4_4(a, st) : fc::launch_fused_4_8(a, st);
     else
         e = (bits_out == 4) ? fc::launch_fused_8_4(a, st) : fc::launch_fused_8_8(a, st);

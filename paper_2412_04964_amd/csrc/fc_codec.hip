@@ -35,6 +35,8 @@ static void launch_q_bits(hipStream_t stream, const uint16_t *x, int64_t n_elems
 hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int group,
                            void *codes, float *scales, float *zeros, hipStream_t stream)
 {
+    if (is_wide_group(bits, group))
+        return launch_quantize_wide(bits, x_f16, n_elems, group, codes, scales, zeros, stream);
     const uint16_t *x = static_cast<const uint16_t *>(x_f16);
     uint8_t *c = static_cast<uint8_t *>(codes);
     if (bits == 4)

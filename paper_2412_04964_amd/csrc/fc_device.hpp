@@ -296,20 +296,13 @@ __device__ __forceinline__ void pack_codes(const float (&v)[EPL], float inv, flo
 // (t3*16 + t2)*16 + ... , every partial sum an integer below 2^24 and therefore
 // exact, and z*(1 + 16 + 16^2 + 16^3) is added once.
 // Otherwise each code is formed literally as in Eq. 2.
-template <int BITS, int EPL, int LPG>
-__device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
-                                              u32 (&word)[EPL * BITS / 32], float &s, float &zf)
+// `mx` is the group's maximum (the largest t of the group decides whether the
+// upper clamp can act at all); inv and zf come from group_params.
+template <int BITS, int EPL>
+__device__ __forceinline__ void pack_lane(const float (&v)[EPL], float inv, float zf, float mx,
+                                          u32 (&word)[EPL * BITS / 32])
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
-    float mn = v[0], mx = v[0];
-#pragma unroll
-    for (int i = 1; i < EPL; ++i) {
-        mn = fminf(mn, v[i]);
-        mx = fmaxf(mx, v[i]);
-    }
-    group_minmax<LPG>(mn, mx, lpg_rt);
-    float inv;
-    group_params<BITS>(mn, mx, s, inv, zf);
     const bool pack_fast = __builtin_amdgcn_ballot_w64(!(fabsf(zf) <= 2048.0f)) == 0;
     if (pack_fast) {
         const float tmax = qmax - zf;
@@ -329,6 +322,63 @@ __device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
             word[w] = acc;
         }
     }
+}
+
+template <int EPL>
+__device__ __forceinline__ void lane_minmax(const float (&v)[EPL], float &mn, float &mx)
+{
+    mn = v[0];
+    mx = v[0];
+#pragma unroll
+    for (int i = 1; i < EPL; ++i) {
+        mn = fminf(mn, v[i]);
+        mx = fmaxf(mx, v[i]);
+    }
+}
+
+template <int BITS, int EPL, int LPG>
+__device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
+                                              u32 (&word)[EPL * BITS / 32], float &s, float &zf)
+{
+    float mn, mx;
+    lane_minmax(v, mn, mx);
+    group_minmax<LPG>(mn, mx, lpg_rt);
+    float inv;
+    group_params<BITS>(mn, mx, s, inv, zf);
+    pack_lane<BITS, EPL>(v, inv, zf, mx, word);
+}
+
+// min / max across the `n_waves` (2 or 4, aligned) wavefronts of a workgroup
+// that share one group; mn / mx are already reduced over each wavefront.  Every
+// wavefront of the workgroup must call it (it contains a barrier).
+__device__ __forceinline__ void cross_wave_minmax(float &mn, float &mx, float (*slot)[2], u32 wave,
+                                                  u32 lane, u32 n_waves)
+{
+    if (lane == 0) {
+        slot[wave][0] = mn;
+        slot[wave][1] = mx;
+    }
+    __syncthreads();
+    const u32 w0 = wave & ~(n_waves - 1u);
+    for (u32 k = 0; k < n_waves; ++k) {
+        mn = fminf(mn, slot[w0 + k][0]);
+        mx = fmaxf(mx, slot[w0 + k][1]);
+    }
+}
+
+// quantize_lane for a run-time group width of 16 ... 256 lanes (up to the whole workgroup)
+template <int BITS, int EPL>
+__device__ __forceinline__ void quantize_lane_any(const float (&v)[EPL], int lpg, float (*slot)[2],
+                                                  u32 wave, u32 lane,
+                                                  u32 (&word)[EPL * BITS / 32], float &s, float &zf)
+{
+    float mn, mx;
+    lane_minmax(v, mn, mx);
+    group_minmax<0>(mn, mx, lpg);
+    if (lpg > 64) cross_wave_minmax(mn, mx, slot, wave, lane, (u32)lpg >> 6);
+    float inv;
+    group_params<BITS>(mn, mx, s, inv, zf);
+    pack_lane<BITS, EPL>(v, inv, zf, mx, word);
 }
 
 struct ZeroConst {
@@ -380,16 +430,9 @@ __device__ __forceinline__ void group_params_sym(float amax, float &s, float &in
 // of the asymmetric path after a bias of 2^(n-1) per digit, and the bias is
 // removed again by flipping each digit's top bit (offset binary -> two's
 // complement).
-template <int BITS, int EPL, int LPG>
-__device__ __forceinline__ void quantize_lane_sym(const float (&v)[EPL], int lpg_rt,
-                                                  u32 (&word)[EPL * BITS / 32], float &s)
+template <int BITS, int EPL>
+__device__ __forceinline__ void pack_lane_sym(const float (&v)[EPL], float inv, u32 (&word)[EPL * BITS / 32])
 {
-    float amax = fabsf(v[0]);
-#pragma unroll
-    for (int i = 1; i < EPL; ++i) amax = fmaxf(amax, fabsf(v[i]));
-    amax = group_max<LPG>(amax, lpg_rt);
-    float inv;
-    group_params_sym<BITS>(amax, s, inv);
     if constexpr (BITS == 4) {
 #pragma unroll
         for (int w = 0; w < EPL / 8; ++w) {
@@ -411,6 +454,40 @@ __device__ __forceinline__ void quantize_lane_sym(const float (&v)[EPL], int lpg
             word[w] = ((u32)lo | ((u32)hi << 16)) ^ 0x80808080u;
         }
     }
+}
+
+template <int EPL>
+__device__ __forceinline__ float lane_absmax(const float (&v)[EPL])
+{
+    float amax = fabsf(v[0]);
+#pragma unroll
+    for (int i = 1; i < EPL; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    return amax;
+}
+
+template <int BITS, int EPL, int LPG>
+__device__ __forceinline__ void quantize_lane_sym(const float (&v)[EPL], int lpg_rt,
+                                                  u32 (&word)[EPL * BITS / 32], float &s)
+{
+    const float amax = group_max<LPG>(lane_absmax(v), lpg_rt);
+    float inv;
+    group_params_sym<BITS>(amax, s, inv);
+    pack_lane_sym<BITS, EPL>(v, inv, word);
+}
+
+template <int BITS, int EPL>
+__device__ __forceinline__ void quantize_lane_sym_any(const float (&v)[EPL], int lpg, float (*slot)[2],
+                                                      u32 wave, u32 lane,
+                                                      u32 (&word)[EPL * BITS / 32], float &s)
+{
+    float amax = group_max<0>(lane_absmax(v), lpg);
+    if (lpg > 64) {
+        float lo = -amax;
+        cross_wave_minmax(lo, amax, slot, wave, lane, (u32)lpg >> 6);
+    }
+    float inv;
+    group_params_sym<BITS>(amax, s, inv);
+    pack_lane_sym<BITS, EPL>(v, inv, word);
 }
 
 // signed codes -> offset binary (q + 2^(n-1)) and the matching "zero-point"
@@ -706,13 +783,14 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
 
     __shared__ __attribute__((aligned(16))) uint8_t landing[kBlockWaves][NSRC][1024];
     __shared__ MetaRec meta[kBlockWaves][NSRC * kMaxGw];
+    __shared__ float slot[LPG == 0 ? kBlockWaves : 1][2];     // cross-wavefront min / max (wide groups)
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kBlockWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
     const int lpg_v = LPG > 0 ? LPG : lpg;
-    const int gw = 64 / lpg_v;                                // groups per wavefront tile
+    const int gw = lpg_v < 64 ? 64 / lpg_v : 1;               // groups per wavefront tile
     const int gw_shift = __builtin_ctz(gw);
     const int entries = NSRC * gw;
 
@@ -761,7 +839,7 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
             meta[wave][idx] = r;
         }
     }
-    const MetaRec *my_meta = &meta[wave][lane / lpg_v];
+    const MetaRec *my_meta = &meta[wave][lane / (u32)lpg_v];  // entry 0 when the group spans the wavefront
 
     float acc[EPL];
 #pragma unroll
@@ -793,7 +871,10 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
     // --- requantize the sums and store
     u32 word[EPL * BITS_OUT / 32];
     float s, zf;
-    quantize_lane<BITS_OUT, EPL, LPG>(acc, lpg, word, s, zf);
+    if constexpr (LPG == 0)
+        quantize_lane_any<BITS_OUT, EPL>(acc, lpg, slot, wave, lane, word, s, zf);
+    else
+        quantize_lane<BITS_OUT, EPL, LPG>(acc, lpg, word, s, zf);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t rz = make_rsrc(zeros_out + g_tile, (n_groups - g_tile) * 4);
@@ -823,6 +904,7 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
     __shared__ __attribute__((aligned(16))) uint8_t landing[kBlockWaves][NSRC][1024];
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kBlockWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
+    __shared__ float slot[LPG == 0 ? kBlockWaves : 1][2];     // cross-wavefront maximum (wide groups)
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
@@ -863,7 +945,10 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
 
     u32 word[EPL * BITS_OUT / 32];
     float s;
-    quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, lpg, word, s);
+    if constexpr (LPG == 0)
+        quantize_lane_sym_any<BITS_OUT, EPL>(acc, lpg, slot, wave, lane, word, s);
+    else
+        quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, lpg, word, s);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
     store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);

@@ -8,7 +8,7 @@
 namespace fc {
 
 // n_elems = tokens*hidden (a multiple of `group`, which is a power of two in
-// [32, 1024]).  All pointers are device pointers.  zeros == nullptr selects the
+// [32, 16384]).  All pointers are device pointers.  zeros == nullptr selects the
 // symmetric quantizer (scales only).
 hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int group,
                            void *codes, float *scales, float *zeros, hipStream_t stream);
@@ -36,6 +36,17 @@ hipError_t launch_fused_4_4(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_4_8(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_8_4(const FusedArgs &a, hipStream_t stream);
 hipError_t launch_fused_8_8(const FusedArgs &a, hipStream_t stream);
+
+// fc_wide.hip holds one-group-per-workgroup kernels for coarse groups.  The
+// stand-alone quantizer uses them for every group wider than one wavefront (64
+// lanes x 128 bits of codes); the fused kernel reduces across the wavefronts of
+// its workgroup itself and hands over only groups wider than its 256-lane tile.
+inline bool is_wide_group(int bits, int group) { return group * bits / 128 > 64; }
+inline bool exceeds_tile(int bits, int group) { return group * bits / 128 > 256; }
+
+hipError_t launch_quantize_wide(int bits, const void *x_f16, int64_t n_elems, int group,
+                                void *codes, float *scales, float *zeros, hipStream_t stream);
+hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipStream_t stream);
 
 inline int log2_int(int v)
 {

@@ -43,7 +43,8 @@ class Workload:
 
 # The five configurations the benchmark contract names, plus the paper's mixed-precision
 # "INT6" setting (4 bit before the reduce, 8 bit before the gather; Section 3.2.3) at the headline shape,
-# and the symmetric quantizer of the paper's ablation (Table 6) at the two prefill shapes.
+# the symmetric quantizer of the paper's ablation (Table 6) at the two prefill shapes, and the
+# coarsest granularity of the block-size study (one group per token) at the headline shape.
 WORKLOADS = {
     "tiny": Workload("tiny", 2, 16, 4096, 8, 8, 128, outlier_frac=0.0),
     "llama3_8b_prefill": Workload("llama3_8b_prefill", 4, 8192, 4096, 8, 8, 128),
@@ -52,6 +53,7 @@ WORKLOADS = {
     "decode": Workload("decode", 8, 8, 8192, 8, 8, 128),
     "llama3_70b_prefill_int6": Workload("llama3_70b_prefill_int6", 4, 8192, 8192, 4, 8, 128),
     "llama3_70b_prefill_sym": Workload("llama3_70b_prefill_sym", 4, 8192, 8192, 4, 4, 128, quantizer="sym"),
+    "llama3_70b_prefill_per_token": Workload("llama3_70b_prefill_per_token", 4, 8192, 8192, 4, 4, 8192),
     "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
 }
 

@@ -49,7 +49,7 @@ def test_quantize_argument_checks(L):
     assert q(P, 4, 256, 128, 5, P, P, P, None) == -2          # bits
     assert q(P, 4, 256, 100, 8, P, P, P, None) == -3          # group not a power of two
     assert q(P, 4, 256, 16, 8, P, P, P, None) == -3           # group too small
-    assert q(P, 4, 4096, 2048, 8, P, P, P, None) == -3        # group too large
+    assert q(P, 4, 32768, 32768, 8, P, P, P, None) == -3      # group too large
     assert q(P, 4, 192, 128, 8, P, P, P, None) == -3          # hidden % group
     assert q(P, -1, 256, 128, 8, P, P, P, None) == -4         # tokens
     assert q(P, 4, 0, 128, 8, P, P, P, None) == -4            # hidden

@@ -1,0 +1,136 @@
+"""GPU parity for coarse granularities: groups of 2048 ... 16384 elements, up to
+one group per token (the block sizes of the paper's granularity study, Section
+3.2.1 and the rotation table of Section 4), asymmetric and symmetric, against
+the CPU oracle, bit for bit.  Run with ``-m gpu`` on an MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs
+from test_gpu_parity import (assert_f16, assert_triplet, dev, first_diff, gpu_dequantize, gpu_fused,
+                             gpu_quantize, oracle_stage1, same_bits, fc)  # noqa: F401
+from test_gpu_parity_sym import (assert_pair, gpu_dequantize_sym, gpu_fused_sym, gpu_quantize_sym,
+                                 oracle_stage1_sym)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+# (tokens, hidden, group): groups spanning one wavefront exactly, 2 and 4 wavefronts, and 2 or 4
+# sub-tiles of a workgroup; several groups per row and one group per row
+CASES = [(5, 4096, 2048), (3, 4096, 4096), (4, 8192, 2048), (3, 8192, 8192), (2, 16384, 4096),
+         (3, 16384, 16384), (1, 32768, 16384)]
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("case", CASES)
+def test_quantize_wide_groups(fc, bits, case):
+    t, h, g = case
+    x = synth_inputs.make_partials(1, t, h, seed=h + g)[0]
+    assert_triplet(gpu_quantize(fc, x, g, bits), oracle.quantize(x, g, bits), "quantize %s b=%d" % (case, bits))
+    assert_pair(gpu_quantize_sym(fc, x, g, bits), oracle.quantize_sym(x, g, bits),
+                "quantize_sym %s b=%d" % (case, bits))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_quantize_wide_extreme_element_positions(fc, bits):
+    # the group's minimum / maximum sits in the first or last lane of any wavefront or sub-tile
+    t, h, g = 16, 8192, 8192
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((t, h)).astype(np.float16)
+    pos = [0, 31, 2047, 2048, 4095, 4096, 6143, 8191]
+    for r in range(t):
+        x[r, pos[r % 8]] = 30.0 + r
+        x[r, pos[(r + 3) % 8]] = -40.0 - r
+    assert_triplet(gpu_quantize(fc, x, g, bits), oracle.quantize(x, g, bits), "extreme positions")
+    assert_pair(gpu_quantize_sym(fc, x, g, bits), oracle.quantize_sym(x, g, bits), "extreme positions sym")
+
+
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 4, 5, 8])
+def test_fused_wide_groups(fc, bits_in, bits_out, n_src):
+    for (t, h, g) in CASES[:6]:
+        x = synth_inputs.make_partials(n_src, t, h, seed=n_src + g)
+        c, s, z = oracle_stage1(x, g, bits_in)
+        want = oracle.dequant_reduce_requant(c, s, z, h, g, bits_in, bits_out)
+        assert_triplet(gpu_fused(fc, c, s, z, h, g, bits_in, bits_out), want,
+                       "fused N=%d %s %d->%d" % (n_src, (t, h, g), bits_in, bits_out))
+        c, s = oracle_stage1_sym(x, g, bits_in)
+        want = oracle.dequant_reduce_requant_sym(c, s, h, g, bits_in, bits_out)
+        assert_pair(gpu_fused_sym(fc, c, s, h, g, bits_in, bits_out), want,
+                    "fused_sym N=%d %s %d->%d" % (n_src, (t, h, g), bits_in, bits_out))
+
+
+@pytest.mark.parametrize("bits_in", [4, 8])
+def test_fused_wide_arbitrary_meta(fc, bits_in):
+    # zero-points outside the fast range, fractional, huge: the literal fp32 path per source
+    rng = np.random.default_rng(11)
+    n_src, t, h, g = 4, 6, 8192, 4096
+    c = rng.integers(0, 256, size=(n_src, t, h * bits_in // 8), dtype=np.uint8)
+    s = np.exp(rng.uniform(-12, 8, size=(n_src, t, h // g))).astype(np.float32)
+    z = np.rint(rng.uniform(-20, 300, size=(n_src, t, h // g))).astype(np.float32)
+    z[0, :, 0] = rng.uniform(-3e6, 3e6, size=t).astype(np.float32)
+    z[1, 1::2, 1] += 0.25
+    z[2, 0] = -1701.0
+    z[2, 1] = 1001.0
+    z[3, 2] = 2.0 ** 24 + 2
+    for bits_out in (4, 8):
+        want = oracle.dequant_reduce_requant(c, s, z, h, g, bits_in, bits_out)
+        assert_triplet(gpu_fused(fc, c, s, z, h, g, bits_in, bits_out), want,
+                       "wide arbitrary meta %d->%d" % (bits_in, bits_out))
+        want = oracle.dequant_reduce_requant_sym(c, s, h, g, bits_in, bits_out)
+        assert_pair(gpu_fused_sym(fc, c, s, h, g, bits_in, bits_out), want,
+                    "wide arbitrary codes sym %d->%d" % (bits_in, bits_out))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_dequantize_wide_groups(fc, bits):
+    for (t, h, g) in CASES:
+        x = synth_inputs.make_partials(1, t, h, seed=5)[0]
+        c, s, z = oracle.quantize(x, g, bits)
+        want = oracle.dequantize(c, s, z, h, g, bits)
+        assert_f16(gpu_dequantize(fc, c, s, z, h, g, bits), want, np.repeat(s, g, axis=1),
+                   "dequantize %s b=%d" % ((t, h, g), bits))
+        c, s = oracle.quantize_sym(x, g, bits)
+        want = oracle.dequantize_sym(c, s, h, g, bits)
+        assert_f16(gpu_dequantize_sym(fc, c, s, h, g, bits), want, np.repeat(s, g, axis=1),
+                   "dequantize_sym %s b=%d" % ((t, h, g), bits))
+
+
+@pytest.mark.parametrize("hidden", [4096, 8192])
+@pytest.mark.parametrize("bits_rs,bits_ag", [(4, 4), (8, 8), (4, 8)])
+def test_allreduce_sim_per_token(fc, hidden, bits_rs, bits_ag):
+    # one group per token: the coarsest point of the paper's granularity study
+    n_src, t = 4, 6
+    x = synth_inputs.make_partials(n_src, t, hidden, seed=hidden + bits_rs)
+    xd = dev(x.view(np.uint16)).view(torch.float16)
+    want = oracle.allreduce_sim(x, hidden, bits_rs, bits_ag)
+    got = fc.allreduce_sim(xd, hidden, bits_rs, bits_ag).cpu().numpy()
+    assert same_bits(got.view(np.uint16), want.view(np.uint16)), first_diff(got.view(np.uint16), want.view(np.uint16))
+    want = oracle.allreduce_sim_sym(x, hidden, bits_rs, bits_ag)
+    got = fc.allreduce_sim_sym(xd, hidden, bits_rs, bits_ag).cpu().numpy()
+    assert same_bits(got.view(np.uint16), want.view(np.uint16)), first_diff(got.view(np.uint16), want.view(np.uint16))
+
+
+def test_per_token_full_size_on_sampled_rows(fc):
+    # the headline shape with one group per token, whole tensor through the GPU
+    w = synth_inputs.WORKLOADS["llama3_70b_prefill"]
+    g = w.hidden
+    x = synth_inputs.make_partials_device(w.n_src, w.tokens, w.hidden, 7, "cuda", w.outlier_frac, w.outlier_gain)
+    rows = np.unique(np.concatenate([[0, w.tokens - 1], np.random.default_rng(3).integers(0, w.tokens, 30)]))
+    ridx = torch.from_numpy(rows).cuda()
+    stage1 = [fc.quantize(x[j], g, w.bits_in) for j in range(w.n_src)]
+    c = torch.stack([p[0] for p in stage1]); s = torch.stack([p[1] for p in stage1])
+    z = torch.stack([p[2] for p in stage1])
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, w.hidden, g, w.bits_in, w.bits_out)
+    y = fc.dequantize(co, so, zo, w.hidden, g, w.bits_out)
+    torch.cuda.synchronize()
+    xs = x[:, ridx].cpu().numpy()
+    oc, os_, oz = oracle_stage1(xs, g, w.bits_in)
+    assert_triplet((c[:, ridx].cpu().numpy(), s[:, ridx].cpu().numpy(), z[:, ridx].cpu().numpy()),
+                   (oc, os_, oz), "per-token stage 1")
+    want = oracle.dequant_reduce_requant(oc, os_, oz, w.hidden, g, w.bits_in, w.bits_out)
+    assert_triplet((co[ridx].cpu().numpy(), so[ridx].cpu().numpy(), zo[ridx].cpu().numpy()), want,
+                   "per-token fused")
+    wy = oracle.dequantize(*want, w.hidden, g, w.bits_out)
+    assert_f16(y[ridx].cpu().numpy(), wy, np.repeat(want[1], g, axis=1), "per-token output")
