@@ -134,3 +134,17 @@ def test_per_token_full_size_on_sampled_rows(fc):
                    "per-token fused")
     wy = oracle.dequantize(*want, w.hidden, g, w.bits_out)
     assert_f16(y[ridx].cpu().numpy(), wy, np.repeat(want[1], g, axis=1), "per-token output")
+
+
+def test_ablation_sweep_matches_oracle_errors(fc):
+    # the error table of the granularity / precision sweep equals what the oracle's outputs give
+    from paper_2412_04964_amd import ablation
+    x = synth_inputs.make_partials(4, 8, 4096, seed=6)
+    rows = ablation.sweep(dev(x.view(np.uint16)).view(torch.float16), [128, 1024, 4096])
+    assert len(rows) == 3 * 2 * 3
+    exact = x.astype(np.float64).sum(0)
+    for r in rows:
+        b_rs, b_ag = ablation.PRECISIONS[r["precision"]]
+        fn = oracle.allreduce_sim_sym if r["quantizer"] == "sym" else oracle.allreduce_sim
+        want = float(np.mean((fn(x, r["group"], b_rs, b_ag).astype(np.float64) - exact) ** 2))
+        assert abs(r["mse"] - want) <= 1e-4 * want, r
