@@ -67,6 +67,23 @@ def lib() -> ctypes.CDLL:
         L.fc_ref_dequant_reduce_requant_sym.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32,
                                                         vp, vp]
         L.fc_ref_allreduce_sim_sym.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp]
+        L.fc_ref_e4m3_to_float.restype = ctypes.c_float
+        L.fc_ref_e4m3_to_float.argtypes = [ctypes.c_uint8]
+        L.fc_ref_float_to_e4m3.restype = ctypes.c_uint8
+        L.fc_ref_float_to_e4m3.argtypes = [ctypes.c_float]
+        L.fc_ref_quantize_group_fp8_f32.restype = None
+        L.fc_ref_quantize_group_fp8_f32.argtypes = [vp, i32, vp, vp]
+        L.fc_ref_quantize_fp8_f32.argtypes = [vp, i64, i64, i32, vp, vp]
+        L.fc_ref_quantize_fp8.argtypes = [vp, i64, i64, i32, vp, vp]
+        L.fc_ref_dequantize_fp8_f32.argtypes = [vp, vp, i64, i64, i32, vp]
+        L.fc_ref_dequantize_fp8.argtypes = [vp, vp, i64, i64, i32, vp]
+        L.fc_ref_dequant_reduce_fp8_f32.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp]
+        L.fc_ref_dequant_reduce_requant_fp8.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp, vp]
+        L.fc_ref_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp]
+        for name in ("fc_ref_quantize_fp8_f32", "fc_ref_quantize_fp8", "fc_ref_dequantize_fp8_f32",
+                     "fc_ref_dequantize_fp8", "fc_ref_dequant_reduce_fp8_f32",
+                     "fc_ref_dequant_reduce_requant_fp8", "fc_ref_allreduce_sim_fp8"):
+            getattr(L, name).restype = i32
         for name in ("fc_ref_quantize_f32", "fc_ref_quantize", "fc_ref_dequantize_f32",
                      "fc_ref_dequantize", "fc_ref_dequant_reduce_f32",
                      "fc_ref_dequant_reduce_requant", "fc_ref_allreduce_sim",
@@ -284,4 +301,87 @@ def allreduce_sim_sym(x_f16, group: int, bits_rs: int, bits_ag: int):
     y = np.zeros((t, h), np.uint16)
     _chk(lib().fc_ref_allreduce_sim_sym(_p(x), n, t, h, group, bits_rs, bits_ag, _p(y)),
          "allreduce_sim_sym")
+    return y.view(np.float16)
+
+
+# --------------------------------------------------------------------------- #
+# FP8 E4M3 per-group symmetric variant: one E4M3 byte per element, scales only
+# --------------------------------------------------------------------------- #
+
+def e4m3_to_float(code: int) -> float:
+    return float(lib().fc_ref_e4m3_to_float(int(code) & 0xFF))
+
+
+def float_to_e4m3(x: float) -> int:
+    return int(lib().fc_ref_float_to_e4m3(float(np.float32(x))))
+
+
+def quantize_group_fp8_f32(x):
+    """one group of fp32 values -> (E4M3 bytes uint8[g], scale)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    q = np.zeros(x.size, np.uint8)
+    s = np.zeros(1, np.float32)
+    lib().fc_ref_quantize_group_fp8_f32(_p(x), x.size, _p(q), _p(s))
+    return q, s[0]
+
+
+def quantize_fp8_f32(x, group: int):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    t, h = x.shape
+    _chk(0 if h % group == 0 else -1, "quantize_fp8_f32")
+    c, s, _ = _alloc_q(t, h, group, 8)
+    _chk(lib().fc_ref_quantize_fp8_f32(_p(x), t, h, group, _p(c), _p(s)), "quantize_fp8_f32")
+    return c, s
+
+
+def quantize_fp8(x_f16, group: int):
+    x = _as_u16(x_f16)
+    t, h = x.shape
+    _chk(0 if h % group == 0 else -1, "quantize_fp8")
+    c, s, _ = _alloc_q(t, h, group, 8)
+    _chk(lib().fc_ref_quantize_fp8(_p(x), t, h, group, _p(c), _p(s)), "quantize_fp8")
+    return c, s
+
+
+def dequantize_fp8_f32(codes, scales, hidden: int, group: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequantize_fp8_f32(_p(codes), _p(scales), t, hidden, group, _p(y)), "dequantize_fp8_f32")
+    return y
+
+
+def dequantize_fp8(codes, scales, hidden: int, group: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.uint16)
+    _chk(lib().fc_ref_dequantize_fp8(_p(codes), _p(scales), t, hidden, group, _p(y)), "dequantize_fp8")
+    return y.view(np.float16)
+
+
+def dequant_reduce_fp8_f32(codes_in, scales_in, hidden: int, group: int):
+    c, s = _stacked_sym(codes_in, scales_in)
+    n, t = c.shape[0], c.shape[1]
+    acc = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequant_reduce_fp8_f32(_p(c), c[0].nbytes, _p(s), s[0].size, n, t, hidden, group,
+                                             _p(acc)), "dequant_reduce_fp8_f32")
+    return acc
+
+
+def dequant_reduce_requant_fp8(codes_in, scales_in, hidden: int, group: int):
+    c, s = _stacked_sym(codes_in, scales_in)
+    n, t = c.shape[0], c.shape[1]
+    co, so, _ = _alloc_q(t, hidden, group, 8)
+    _chk(lib().fc_ref_dequant_reduce_requant_fp8(_p(c), c[0].nbytes, _p(s), s[0].size, n, t, hidden,
+                                                 group, _p(co), _p(so)), "dequant_reduce_requant_fp8")
+    return co, so
+
+
+def allreduce_sim_fp8(x_f16, group: int):
+    x = _as_u16(x_f16)
+    n, t, h = x.shape
+    y = np.zeros((t, h), np.uint16)
+    _chk(lib().fc_ref_allreduce_sim_fp8(_p(x), n, t, h, group, _p(y)), "allreduce_sim_fp8")
     return y.view(np.float16)

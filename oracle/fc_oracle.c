@@ -44,6 +44,21 @@
  *   S3  codes are signed, clamped to [-2^(n-1), 2^(n-1)-1] as Eq. 4 says, and
  *       stored in two's complement in the same packing as R8;
  *   S4  Dequantize is x^ = q * s; the N-way sum is acc = fma(q_j, s_j, acc).
+ * FP8 variant (the FP8_Sym rows of the precision table and of the rotation
+ * table, "FP8 and FP4 Format" in the Appendix): the fc_ref_*_fp8 functions, with
+ *   F1  the code is one OCP FP8 E4M3 number per byte (Micikevicius et al. 2022,
+ *       which the paper cites): 1 sign, 4 exponent bits with bias 7, 3 fraction
+ *       bits, subnormals of step 2^-9, no infinities, S.1111.111 is NaN, largest
+ *       finite value 448;
+ *   F2  per-group symmetric scale s = max|X| / 448 in fp32 (the paper prints
+ *       no formula for FP8; this is Eq. 3 with the format's largest value in
+ *       place of 2^(n-1) - 1); s below FLT_MIN -> s = 1 as in S2;
+ *   F3  q = E4M3(X * (1/s)): round to nearest, ties to even fraction, sign kept
+ *       (so a negative value that rounds to zero gives -0, byte 0x80);
+ *       magnitudes beyond 448 saturate to 448 (cannot happen for a group's own
+ *       values, as with the clamps of Eq. 4);
+ *   F4  Dequantize is x^ = value(q) * s; the N-way sum is
+ *       acc = fma(value(q_j), s_j, acc) from +0.
  * Domain: finite inputs.  NaN / Inf inputs: parity unpinned.
  *
  * Build: cc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
@@ -504,6 +519,179 @@ int fc_ref_allreduce_sim_sym(const uint16_t *x_f16, int n_src, int64_t tokens, i
                                                bits_rs, bits_ag, c2, s2);
     if (rc == FC_REF_OK)
         rc = fc_ref_dequantize_sym(c2, s2, tokens, hidden, group, bits_ag, y_f16);
+    free(c1); free(s1); free(c2); free(s2);
+    return rc;
+}
+
+/* ======================================================================== */
+/* FP8 E4M3 per-group symmetric quantization -- readings F1-F4 above.        */
+/* ======================================================================== */
+
+/* value of one E4M3 byte (F1) */
+float fc_ref_e4m3_to_float(uint8_t c)
+{
+    const int sign = (c >> 7) & 1;
+    const int e = (c >> 3) & 0xF;
+    const int f = c & 7;
+    double v;
+    if (e == 15 && f == 7)
+        v = (double)NAN;
+    else if (e == 0)
+        v = ldexp((double)f, -9);                /* zero or subnormal: f * 2^-9 */
+    else
+        v = ldexp((double)(8 + f), e - 10);      /* (1 + f/8) * 2^(e-7) */
+    return (float)(sign ? -v : v);
+}
+
+/* nearest E4M3 number, ties to even, saturating at +-448 (F3) */
+uint8_t fc_ref_float_to_e4m3(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    const uint8_t sign = (uint8_t)((u >> 24) & 0x80u);
+    if (isnan(x)) return (uint8_t)(sign | 0x7Fu);
+    const double a = fabs((double)x);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7Eu);            /* 448 = 0.1111.110 */
+    if (a == 0.0) return sign;
+    int e2;
+    (void)frexp(a, &e2);
+    int e = e2 - 1;                              /* a in [2^e, 2^(e+1)) */
+    if (e < -6) e = -6;                          /* subnormals share the grid of the first binade */
+    /* spacing of E4M3 numbers around a is 2^(e-3); a / spacing is exact in
+       double and nearbyint rounds half to even */
+    uint32_t mant = (uint32_t)nearbyint(ldexp(a, 3 - e));      /* in [0, 16] */
+    int be = e + 7;
+    if (mant >= 16u) { mant = 8u; be += 1; }
+    if (mant < 8u) return (uint8_t)(sign | mant);              /* subnormal (or zero) */
+    return (uint8_t)(sign | ((uint32_t)be << 3) | (mant - 8u)); /* be <= 15 and never 1111.111 since a < 448 */
+}
+
+/* F2-F3 on ONE group */
+void fc_ref_quantize_group_fp8_f32(const float *x, int g, uint8_t *q, float *scale)
+{
+    float amax = 0.0f;
+    for (int k = 0; k < g; ++k) {
+        const float a = fabsf(x[k]);
+        if (a > amax) amax = a;
+    }
+    float s = amax / 448.0f;
+    if (!(s >= FLT_MIN)) s = 1.0f;
+    const float inv = 1.0f / s;
+    for (int k = 0; k < g; ++k) q[k] = fc_ref_float_to_e4m3(x[k] * inv);
+    *scale = s;
+}
+
+int fc_ref_quantize_fp8_f32(const float *x, int64_t tokens, int64_t hidden, int group,
+                            uint8_t *codes, float *scales)
+{
+    if (!check_shape(tokens, hidden, group, 8)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x || !codes || !scales) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t c = 0; c < gpr; ++c)
+            fc_ref_quantize_group_fp8_f32(x + t * hidden + c * group, group,
+                                          codes + t * hidden + c * group, &scales[t * gpr + c]);
+    return FC_REF_OK;
+}
+
+int fc_ref_quantize_fp8(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group,
+                        uint8_t *codes, float *scales)
+{
+    if (!check_shape(tokens, hidden, group, 8)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x_f16 || !codes || !scales) return FC_REF_BAD_ARG;
+    float *xf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!xf) return FC_REF_NO_MEM;
+    for (int64_t i = 0; i < tokens * hidden; ++i) xf[i] = fc_ref_half_to_float(x_f16[i]);
+    const int rc = fc_ref_quantize_fp8_f32(xf, tokens, hidden, group, codes, scales);
+    free(xf);
+    return rc;
+}
+
+/* x^ = value(q) * s (F4), fp32 */
+int fc_ref_dequantize_fp8_f32(const uint8_t *codes, const float *scales,
+                              int64_t tokens, int64_t hidden, int group, float *y)
+{
+    if (!check_shape(tokens, hidden, group, 8)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !y) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h)
+            y[t * hidden + h] = fc_ref_e4m3_to_float(codes[t * hidden + h]) * scales[t * gpr + h / group];
+    return FC_REF_OK;
+}
+
+int fc_ref_dequantize_fp8(const uint8_t *codes, const float *scales,
+                          int64_t tokens, int64_t hidden, int group, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, 8)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !y_f16) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h)
+            y_f16[t * hidden + h] = fc_ref_float_to_half(
+                fc_ref_e4m3_to_float(codes[t * hidden + h]) * scales[t * gpr + h / group]);
+    return FC_REF_OK;
+}
+
+int fc_ref_dequant_reduce_fp8_f32(const uint8_t *codes_in, int64_t codes_stride,
+                                  const float *scales_in, int64_t meta_stride,
+                                  int n_src, int64_t tokens, int64_t hidden, int group, float *acc)
+{
+    if (!check_shape(tokens, hidden, group, 8) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes_in || !scales_in || !acc) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            float a = 0.0f;
+            for (int j = 0; j < n_src; ++j)
+                a = fmaf(fc_ref_e4m3_to_float(codes_in[(int64_t)j * codes_stride + t * hidden + h]),
+                         scales_in[(int64_t)j * meta_stride + gi], a);
+            acc[t * hidden + h] = a;
+        }
+    return FC_REF_OK;
+}
+
+int fc_ref_dequant_reduce_requant_fp8(const uint8_t *codes_in, int64_t codes_stride,
+                                      const float *scales_in, int64_t meta_stride,
+                                      int n_src, int64_t tokens, int64_t hidden, int group,
+                                      uint8_t *codes_out, float *scales_out)
+{
+    if (!check_shape(tokens, hidden, group, 8) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    float *acc = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!acc) return FC_REF_NO_MEM;
+    int rc = fc_ref_dequant_reduce_fp8_f32(codes_in, codes_stride, scales_in, meta_stride, n_src,
+                                           tokens, hidden, group, acc);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_quantize_fp8_f32(acc, tokens, hidden, group, codes_out, scales_out);
+    free(acc);
+    return rc;
+}
+
+int fc_ref_allreduce_sim_fp8(const uint16_t *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                             int group, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, 8) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    const int64_t m = tokens * hidden, ng = m / group;
+    uint8_t *c1 = (uint8_t *)malloc((size_t)(m * n_src));
+    float *s1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    uint8_t *c2 = (uint8_t *)malloc((size_t)m);
+    float *s2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    int rc = (c1 && s1 && c2 && s2) ? FC_REF_OK : FC_REF_NO_MEM;
+    for (int j = 0; rc == FC_REF_OK && j < n_src; ++j)
+        rc = fc_ref_quantize_fp8(x_f16 + (int64_t)j * m, tokens, hidden, group,
+                                 c1 + (int64_t)j * m, s1 + (int64_t)j * ng);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequant_reduce_requant_fp8(c1, m, s1, ng, n_src, tokens, hidden, group, c2, s2);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequantize_fp8(c2, s2, tokens, hidden, group, y_f16);
     free(c1); free(s1); free(c2); free(s2);
     return rc;
 }
