@@ -77,15 +77,20 @@ def cpu_baseline(w, x_host, budget_s=20.0):
     if est * 3 > budget_s:
         rows = max(16, int(w.tokens * budget_s / (est * 3)))
     xs = x_host[:, :rows]
-    sym = w.quantizer == "sym"
-    parts = [(oracle.quantize_sym if sym else oracle.quantize)(xs[j], w.group, w.bits_in)
-             for j in range(w.n_src)]
+    sym, fp8 = w.quantizer == "sym", w.quantizer == "fp8"
+    if fp8:
+        parts = [oracle.quantize_fp8(xs[j], w.group) for j in range(w.n_src)]
+    else:
+        parts = [(oracle.quantize_sym if sym else oracle.quantize)(xs[j], w.group, w.bits_in)
+                 for j in range(w.n_src)]
     c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
-    z = None if sym else np.stack([p[2] for p in parts])
+    z = None if (sym or fp8) else np.stack([p[2] for p in parts])
     best = None
     for _ in range(2):
         t0 = time.perf_counter()
-        if sym:
+        if fp8:
+            oracle.dequant_reduce_requant_fp8(c, s, w.hidden, w.group)
+        elif sym:
             oracle.dequant_reduce_requant_sym(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
         else:
             oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
@@ -148,24 +153,30 @@ def main():
     Z2 = [torch.empty_like(S2[0]) for _ in range(B)]
     Y = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in range(B)]
 
-    sym = w.quantizer == "sym"
+    sym, fp8 = w.quantizer == "sym", w.quantizer == "fp8"
 
     def stage_quantize(k):
         for j in range(N):
-            if sym:
+            if fp8:
+                fc.quantize_fp8(X[k][j], g, out=(C1[k][j], S1[k][j]))
+            elif sym:
                 fc.quantize_sym(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j]))
             else:
                 fc.quantize(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j], Z1[k][j]))
 
     def stage_fused(k):
-        if sym:
+        if fp8:
+            fc.dequant_reduce_requant_fp8(C1[k], S1[k], H, g, out=(C2[k], S2[k]))
+        elif sym:
             fc.dequant_reduce_requant_sym(C1[k], S1[k], H, g, w.bits_in, w.bits_out, out=(C2[k], S2[k]))
         else:
             fc.dequant_reduce_requant(C1[k], S1[k], Z1[k], H, g, w.bits_in, w.bits_out,
                                       out=(C2[k], S2[k], Z2[k]))
 
     def stage_dequantize(k):
-        if sym:
+        if fp8:
+            fc.dequantize_fp8(C2[k], S2[k], H, g, out=Y[k])
+        elif sym:
             fc.dequantize_sym(C2[k], S2[k], H, g, w.bits_out, out=Y[k])
         else:
             fc.dequantize(C2[k], S2[k], Z2[k], H, g, w.bits_out, out=Y[k])
@@ -231,9 +242,10 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "%s: N=%d partial fp16 tensors of %d tokens x %d hidden, N(0,1) with %g%% outlier "
-                        "channels x%g, INT%d->INT%d %s, group %d"
-                        % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain, w.bits_in, w.bits_out,
-                           "symmetric" if sym else "asymmetric", g),
+                        "channels x%g, %s, group %d"
+                        % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain,
+                           "FP8 E4M3 -> FP8 E4M3 symmetric" if fp8 else
+                           "INT%d->INT%d %s" % (w.bits_in, w.bits_out, "symmetric" if sym else "asymmetric"), g),
             "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
             "volumes_per_step": B,
             "stage_order": "volume-major (dependent)" if a.dependent else "stage-major over the batch",
@@ -248,7 +260,8 @@ def main():
             "whole_path_GBps": round(B * vol_bytes / (wall / a.steps) / 1e9, 1),
         },
         "roofline": {
-            "kernel": "k_dequant_reduce_requant%s<%d,%d,%d>" % ("_sym" if sym else "", w.bits_in, w.bits_out, N),
+            "kernel": "k_dequant_reduce_requant%s<%d,%d,%d>%s" % ("_sym" if (sym or fp8) else "", w.bits_in, w.bits_out,
+                                                                 N, " (E4M3)" if fp8 else ""),
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,

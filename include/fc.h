@@ -167,6 +167,35 @@ FC_API int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, in
                                 int group, int bits_rs, int bits_ag, void *y_f16,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * FP8 variant (the FP8_Sym rows of the paper's precision table and rotation table;
+ * format: Appendix "FP8 and FP4 Format").  Layouts and rules as for the 8-bit symmetric
+ * variant, except that each code byte is one OCP FP8 E4M3 number (1 sign, 4 exponent
+ * bits with bias 7, 3 fraction bits, subnormals, no infinities, largest value 448).
+ * Results are bit-identical to evaluating, for every group,
+ *     s   = max|x| / 448                         one IEEE divide
+ *     if !(s >= FLT_MIN): s = 1                  (all-zero group)
+ *     inv = 1 / s                                 one IEEE divide
+ *     q   = E4M3(x * inv)     nearest, ties to the even fraction, sign kept (-0 is byte 0x80)
+ * Dequantize: x^ = value(q) * s.  ReduceSum: acc = +0; acc = fma(value(q_j), s_j, acc).
+ * Input bytes 0x7F / 0xFF (NaN) are outside the domain.
+ */
+FC_API int fc_quantize_fp8(const void *x_f16, int64_t tokens, int64_t hidden, int group,
+                           void *codes, float *scales, void *hip_stream);
+
+FC_API int fc_dequant_reduce_requant_fp8(const void *codes_in, int64_t codes_src_stride_bytes,
+                                         const float *scales_in, int64_t meta_src_stride_elems,
+                                         int n_src, int64_t tokens, int64_t hidden, int group,
+                                         void *codes_out, float *scales_out, void *hip_stream);
+
+FC_API int fc_dequantize_fp8(const void *codes, const float *scales,
+                             int64_t tokens, int64_t hidden, int group, void *y_f16, void *hip_stream);
+
+/* Algorithm 1 end to end with FP8 on both sides; workspace of
+   fc_allreduce_sim_workspace_bytes(n_src, tokens, hidden, group, 8, 8) bytes suffices. */
+FC_API int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, int64_t hidden, int group,
+                                void *y_f16, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);
 

@@ -9,23 +9,28 @@ present the compute calls fail loudly.
 from .binding import (  # noqa: F401
     FcError,
     allreduce_sim,
+    allreduce_sim_fp8,
     allreduce_sim_sym,
     allreduce_sim_workspace_bytes,
     dequant_reduce_requant,
+    dequant_reduce_requant_fp8,
     dequant_reduce_requant_sym,
     dequantize,
+    dequantize_fp8,
     dequantize_sym,
     last_hip_error,
     lib,
     lib_path,
     quantize,
+    quantize_fp8,
     quantize_sym,
     strerror,
     version,
 )
 
 __all__ = [
-    "FcError", "allreduce_sim", "allreduce_sim_sym", "allreduce_sim_workspace_bytes",
-    "dequant_reduce_requant", "dequant_reduce_requant_sym", "dequantize", "dequantize_sym",
-    "last_hip_error", "lib", "lib_path", "quantize", "quantize_sym", "strerror", "version",
+    "FcError", "allreduce_sim", "allreduce_sim_fp8", "allreduce_sim_sym", "allreduce_sim_workspace_bytes",
+    "dequant_reduce_requant", "dequant_reduce_requant_fp8", "dequant_reduce_requant_sym", "dequantize",
+    "dequantize_fp8", "dequantize_sym", "last_hip_error", "lib", "lib_path", "quantize", "quantize_fp8",
+    "quantize_sym", "strerror", "version",
 ]

@@ -59,6 +59,14 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize_sym.restype = i32
         L.fc_allreduce_sim_sym.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim_sym.restype = i32
+        L.fc_quantize_fp8.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+        L.fc_quantize_fp8.restype = i32
+        L.fc_dequant_reduce_requant_fp8.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp, vp, vp]
+        L.fc_dequant_reduce_requant_fp8.restype = i32
+        L.fc_dequantize_fp8.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+        L.fc_dequantize_fp8.restype = i32
+        L.fc_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp, vp, sz, vp]
+        L.fc_allreduce_sim_fp8.restype = i32
         L.fc_strerror.argtypes = [i32]
         L.fc_strerror.restype = ctypes.c_char_p
         L.fc_last_hip_error.argtypes = []
@@ -271,4 +279,77 @@ def allreduce_sim_sym(x, group: int, bits_rs: int, bits_ag: int, out=None, works
     _check(lib().fc_allreduce_sim_sym(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
                                       workspace.data_ptr(), workspace.numel(), _stream()),
            "fc_allreduce_sim_sym")
+    return y
+
+
+# ---- FP8 E4M3 variant: one E4M3 byte per element, scales only ----
+
+def quantize_fp8(x, group: int, out=None):
+    """fc_quantize_fp8.  x: float16 [tokens, hidden] -> (E4M3 bytes u8 [tokens, hidden],
+    scales f32 [tokens, hidden/group])."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    t, h = x.shape
+    if out is None:
+        if group <= 0 or h % group:
+            _check(lib().fc_quantize_fp8(None, t, h, group, None, None, None), "fc_quantize_fp8")
+        codes = torch.empty((t, h), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
+    else:
+        codes, scales = out
+        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    _check(lib().fc_quantize_fp8(x.data_ptr(), t, h, group, codes.data_ptr(), scales.data_ptr(), _stream()),
+           "fc_quantize_fp8")
+    return codes, scales
+
+
+def dequant_reduce_requant_fp8(codes_in, scales_in, hidden: int, group: int, out=None):
+    """fc_dequant_reduce_requant_fp8.  codes_in u8 [N, tokens, hidden], scales_in f32 [N, tokens, hidden/group]."""
+    torch = _torch()
+    _dev(codes_in, torch.uint8, "codes_in"); _dev(scales_in, torch.float32, "scales_in")
+    n, t = codes_in.shape[0], codes_in.shape[1]
+    if out is None:
+        if group <= 0 or hidden % group:
+            _check(lib().fc_dequant_reduce_requant_fp8(None, 0, None, 0, n, t, hidden, group, None, None, None),
+                   "fc_dequant_reduce_requant_fp8")
+        codes = torch.empty((t, hidden), dtype=torch.uint8, device=codes_in.device)
+        scales = torch.empty((t, hidden // group), dtype=torch.float32, device=codes_in.device)
+    else:
+        codes, scales = out
+        _dev(codes, torch.uint8, "codes_out"); _dev(scales, torch.float32, "scales_out")
+    cstride = codes_in.stride(0) if n > 1 else 0
+    mstride = scales_in.stride(0) if n > 1 else 0
+    _check(lib().fc_dequant_reduce_requant_fp8(
+        codes_in.data_ptr(), cstride, scales_in.data_ptr(), mstride, n, t, hidden, group,
+        codes.data_ptr(), scales.data_ptr(), _stream()), "fc_dequant_reduce_requant_fp8")
+    return codes, scales
+
+
+def dequantize_fp8(codes, scales, hidden: int, group: int, out=None):
+    """fc_dequantize_fp8 -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    t = codes.shape[0]
+    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_dequantize_fp8(codes.data_ptr(), scales.data_ptr(), t, hidden, group, y.data_ptr(),
+                                   _stream()), "fc_dequantize_fp8")
+    return y
+
+
+def allreduce_sim_fp8(x, group: int, out=None, workspace=None):
+    """fc_allreduce_sim_fp8.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    n, t, h = x.shape
+    need = allreduce_sim_workspace_bytes(n, t, h, group, 8, 8)
+    if need == 0 and t != 0:
+        _check(lib().fc_allreduce_sim_fp8(None, n, t, h, group, None, None, 0, None), "fc_allreduce_sim_fp8")
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_allreduce_sim_fp8(x.data_ptr(), n, t, h, group, y.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel(), _stream()), "fc_allreduce_sim_fp8")
     return y

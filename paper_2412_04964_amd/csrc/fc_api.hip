@@ -68,11 +68,12 @@ SimLayout sim_layout(int n_src, int64_t n_elems, int group, int bits_rs, int bit
     return L;
 }
 
-// The asymmetric and symmetric entry points share these; `sym` drops the
-// zero-point arrays (passed as nullptr to the launchers).
-int quantize_impl(bool sym, const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+// All quantizer variants share these; every codec but the asymmetric one drops
+// the zero-point arrays (passed as nullptr to the launchers).
+int quantize_impl(int codec, const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                   void *codes, float *scales, float *zeros, void *hip_stream)
 {
+    const bool sym = codec != fc::CODEC_ASYM;
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits, &n);
     if (rc != FC_OK) return rc;
@@ -80,15 +81,16 @@ int quantize_impl(bool sym, const void *x_f16, int64_t tokens, int64_t hidden, i
     if (!x_f16 || !codes || !scales || (!sym && !zeros)) return FC_ERR_NULL;
     if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || (!sym && !aligned16(zeros)))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_quantize(bits, x_f16, n, group, codes, scales, sym ? nullptr : zeros,
+    return hip_result(fc::launch_quantize(bits, codec, x_f16, n, group, codes, scales, sym ? nullptr : zeros,
                                           static_cast<hipStream_t>(hip_stream)));
 }
 
-int fused_impl(bool sym, const void *codes_in, int64_t codes_src_stride_bytes,
+int fused_impl(int codec, const void *codes_in, int64_t codes_src_stride_bytes,
                const float *scales_in, const float *zeros_in, int64_t meta_src_stride_elems,
                int n_src, int64_t tokens, int64_t hidden, int group, int bits_in, int bits_out,
                void *codes_out, float *scales_out, float *zeros_out, void *hip_stream)
 {
+    const bool sym = codec != fc::CODEC_ASYM;
     int64_t n = 0;
     int rc = check_shape(tokens, hidden, group, bits_in, &n);
     if (rc != FC_OK) return rc;
@@ -110,6 +112,7 @@ int fused_impl(bool sym, const void *codes_in, int64_t codes_src_stride_bytes,
         return FC_ERR_ALIGN;
 
     fc::FusedArgs a;
+    a.codec = codec;
     a.codes_in = codes_in;
     a.codes_stride = codes_src_stride_bytes;
     a.scales_in = scales_in;
@@ -132,9 +135,10 @@ int fused_impl(bool sym, const void *codes_in, int64_t codes_src_stride_bytes,
     return hip_result(e);
 }
 
-int dequantize_impl(bool sym, const void *codes, const float *scales, const float *zeros,
+int dequantize_impl(int codec, const void *codes, const float *scales, const float *zeros,
                     int64_t tokens, int64_t hidden, int group, int bits, void *y_f16, void *hip_stream)
 {
+    const bool sym = codec != fc::CODEC_ASYM;
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits, &n);
     if (rc != FC_OK) return rc;
@@ -142,11 +146,11 @@ int dequantize_impl(bool sym, const void *codes, const float *scales, const floa
     if (!codes || !scales || !y_f16 || (!sym && !zeros)) return FC_ERR_NULL;
     if (!aligned16(codes) || !aligned16(scales) || !aligned16(y_f16) || (!sym && !aligned16(zeros)))
         return FC_ERR_ALIGN;
-    return hip_result(fc::launch_dequantize(bits, codes, scales, sym ? nullptr : zeros, n, group, y_f16,
+    return hip_result(fc::launch_dequantize(bits, codec, codes, scales, sym ? nullptr : zeros, n, group, y_f16,
                                             static_cast<hipStream_t>(hip_stream)));
 }
 
-int allreduce_sim_impl(bool sym, const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
                        int group, int bits_rs, int bits_ag, void *y_f16,
                        void *workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -165,21 +169,21 @@ int allreduce_sim_impl(bool sym, const void *x_f16, int n_src, int64_t tokens, i
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
     for (int j = 0; j < n_src; ++j) {
-        const int q = quantize_impl(sym, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
+        const int q = quantize_impl(codec, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
                                     ws + L.off_codes1 + (size_t)j * L.codes_rs,
                                     reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
                                     reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta),
                                     hip_stream);
         if (q != FC_OK) return q;
     }
-    const int f = fused_impl(sym, ws + L.off_codes1, (int64_t)L.codes_rs,
+    const int f = fused_impl(codec, ws + L.off_codes1, (int64_t)L.codes_rs,
                              reinterpret_cast<const float *>(ws + L.off_scales1),
                              reinterpret_cast<const float *>(ws + L.off_zeros1),
                              (int64_t)(L.meta / sizeof(float)), n_src, tokens, hidden, group, bits_rs,
                              bits_ag, ws + L.off_codes2, reinterpret_cast<float *>(ws + L.off_scales2),
                              reinterpret_cast<float *>(ws + L.off_zeros2), hip_stream);
     if (f != FC_OK) return f;
-    return dequantize_impl(sym, ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
+    return dequantize_impl(codec, ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
                            reinterpret_cast<const float *>(ws + L.off_zeros2), tokens, hidden, group,
                            bits_ag, y_f16, hip_stream);
 }
@@ -191,13 +195,13 @@ extern "C" {
 int fc_quantize(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                 void *codes, float *scales, float *zeros, void *hip_stream)
 {
-    return quantize_impl(false, x_f16, tokens, hidden, group, bits, codes, scales, zeros, hip_stream);
+    return quantize_impl(fc::CODEC_ASYM, x_f16, tokens, hidden, group, bits, codes, scales, zeros, hip_stream);
 }
 
 int fc_quantize_sym(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                     void *codes, float *scales, void *hip_stream)
 {
-    return quantize_impl(true, x_f16, tokens, hidden, group, bits, codes, scales, nullptr, hip_stream);
+    return quantize_impl(fc::CODEC_SYM, x_f16, tokens, hidden, group, bits, codes, scales, nullptr, hip_stream);
 }
 
 int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_bytes,
@@ -208,7 +212,7 @@ int fc_dequant_reduce_requant(const void *codes_in, int64_t codes_src_stride_byt
                               void *codes_out, float *scales_out, float *zeros_out,
                               void *hip_stream)
 {
-    return fused_impl(false, codes_in, codes_src_stride_bytes, scales_in, zeros_in, meta_src_stride_elems,
+    return fused_impl(fc::CODEC_ASYM, codes_in, codes_src_stride_bytes, scales_in, zeros_in, meta_src_stride_elems,
                       n_src, tokens, hidden, group, bits_in, bits_out, codes_out, scales_out, zeros_out,
                       hip_stream);
 }
@@ -219,7 +223,7 @@ int fc_dequant_reduce_requant_sym(const void *codes_in, int64_t codes_src_stride
                                   int bits_in, int bits_out,
                                   void *codes_out, float *scales_out, void *hip_stream)
 {
-    return fused_impl(true, codes_in, codes_src_stride_bytes, scales_in, nullptr, meta_src_stride_elems,
+    return fused_impl(fc::CODEC_SYM, codes_in, codes_src_stride_bytes, scales_in, nullptr, meta_src_stride_elems,
                       n_src, tokens, hidden, group, bits_in, bits_out, codes_out, scales_out, nullptr,
                       hip_stream);
 }
@@ -228,14 +232,14 @@ int fc_dequantize(const void *codes, const float *scales, const float *zeros,
                   int64_t tokens, int64_t hidden, int group, int bits,
                   void *y_f16, void *hip_stream)
 {
-    return dequantize_impl(false, codes, scales, zeros, tokens, hidden, group, bits, y_f16, hip_stream);
+    return dequantize_impl(fc::CODEC_ASYM, codes, scales, zeros, tokens, hidden, group, bits, y_f16, hip_stream);
 }
 
 int fc_dequantize_sym(const void *codes, const float *scales,
                       int64_t tokens, int64_t hidden, int group, int bits,
                       void *y_f16, void *hip_stream)
 {
-    return dequantize_impl(true, codes, scales, nullptr, tokens, hidden, group, bits, y_f16, hip_stream);
+    return dequantize_impl(fc::CODEC_SYM, codes, scales, nullptr, tokens, hidden, group, bits, y_f16, hip_stream);
 }
 
 size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_t hidden, int group,
@@ -252,7 +256,7 @@ int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidde
                      int group, int bits_rs, int bits_ag, void *y_f16,
                      void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return allreduce_sim_impl(false, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+    return allreduce_sim_impl(fc::CODEC_ASYM, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
                               workspace, workspace_bytes, hip_stream);
 }
 
@@ -260,7 +264,36 @@ int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, int64_t h
                          int group, int bits_rs, int bits_ag, void *y_f16,
                          void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return allreduce_sim_impl(true, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+    return allreduce_sim_impl(fc::CODEC_SYM, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+                              workspace, workspace_bytes, hip_stream);
+}
+
+int fc_quantize_fp8(const void *x_f16, int64_t tokens, int64_t hidden, int group,
+                    void *codes, float *scales, void *hip_stream)
+{
+    return quantize_impl(fc::CODEC_FP8, x_f16, tokens, hidden, group, 8, codes, scales, nullptr, hip_stream);
+}
+
+int fc_dequant_reduce_requant_fp8(const void *codes_in, int64_t codes_src_stride_bytes,
+                                  const float *scales_in, int64_t meta_src_stride_elems,
+                                  int n_src, int64_t tokens, int64_t hidden, int group,
+                                  void *codes_out, float *scales_out, void *hip_stream)
+{
+    return fused_impl(fc::CODEC_FP8, codes_in, codes_src_stride_bytes, scales_in, nullptr,
+                      meta_src_stride_elems, n_src, tokens, hidden, group, 8, 8, codes_out, scales_out,
+                      nullptr, hip_stream);
+}
+
+int fc_dequantize_fp8(const void *codes, const float *scales, int64_t tokens, int64_t hidden, int group,
+                      void *y_f16, void *hip_stream)
+{
+    return dequantize_impl(fc::CODEC_FP8, codes, scales, nullptr, tokens, hidden, group, 8, y_f16, hip_stream);
+}
+
+int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, int64_t hidden, int group,
+                         void *y_f16, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return allreduce_sim_impl(fc::CODEC_FP8, x_f16, n_src, tokens, hidden, group, 8, 8, y_f16,
                               workspace, workspace_bytes, hip_stream);
 }
 

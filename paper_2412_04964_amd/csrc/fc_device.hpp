@@ -40,6 +40,11 @@ constexpr int kBlockWaves = kBlockThreads / 64;
 #define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads)
 #endif
 
+// quantizer selected by a template argument of the kernels
+constexpr int kAsym = 0;    // Eq. 1-2: unsigned codes, scale and zero-point
+constexpr int kSym = 1;     // Eq. 3-4: signed codes, scale only
+constexpr int kFp8 = 2;     // FP8 E4M3 bytes, scale only (8-bit only)
+
 // elements per lane for a given code width: one 128-bit access of codes
 constexpr int lane_elems(int bits) { return 128 / bits; }
 constexpr int block_elems(int bits) { return kBlockThreads * lane_elems(bits); }
@@ -404,12 +409,14 @@ __device__ __forceinline__ float group_max(float m, int lpg_rt)
     return m;
 }
 
-// Eq. 3 with the same exhaustively checked division sequences as group_params
-// (r/7 and r/127 match the IEEE quotient for every positive fp32 as well).
-template <int BITS>
-__device__ __forceinline__ void group_params_sym(float amax, float &s, float &inv)
+// Eq. 3 (scale = max|X| / QM) with the same exhaustively checked division
+// sequences as group_params: r/7, r/127 and r/448 match the IEEE quotient for
+// every positive fp32 whose quotient is at least FLT_MIN, and smaller quotients
+// are replaced by 1 on both sides.
+template <int QM>
+__device__ __forceinline__ void group_params_absmax(float amax, float &s, float &inv)
 {
-    constexpr float qm = (float)((1 << (BITS - 1)) - 1);
+    constexpr float qm = (float)QM;
     constexpr float c = 1.0f / qm;
     const float q0 = amax * c;
     const float e = fmaf(-qm, q0, amax);
@@ -422,6 +429,12 @@ __device__ __forceinline__ void group_params_sym(float amax, float &s, float &in
     } else {
         inv = 1.0f / s;
     }
+}
+
+template <int BITS>
+__device__ __forceinline__ void group_params_sym(float amax, float &s, float &inv)
+{
+    group_params_absmax<(1 << (BITS - 1)) - 1>(amax, s, inv);
 }
 
 // Symmetric FinegrainedQuantize of the lane's EPL values.  |x| <= amax makes
@@ -488,6 +501,75 @@ __device__ __forceinline__ void quantize_lane_sym_any(const float (&v)[EPL], int
     float inv;
     group_params_sym<BITS>(amax, s, inv);
     pack_lane_sym<BITS, EPL>(v, inv, word);
+}
+
+// ---------------------------------------------------------------------------
+// FP8 variant (the paper's FP8_Sym rows): one OCP E4M3 byte per element,
+// s = max|X| / 448, q = E4M3(X * (1/s)) to nearest-even, x^ = value(q) * s.
+// gfx950's v_cvt_pk_fp8_f32 / v_cvt_pk_f32_fp8 implement exactly this format
+// (round to nearest even, subnormals, signed zero; checked against a bitwise
+// reference for every fp32 pattern up to |x| = 464, beyond which the hardware
+// returns NaN instead of saturating).  |X * (1/s)| never exceeds
+// 448 * (1 + 2^-22), which rounds to 448, so no clamp is needed.
+// ---------------------------------------------------------------------------
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int EPL>
+__device__ __forceinline__ void pack_lane_fp8(const float (&v)[EPL], float inv, u32 (&word)[EPL / 4])
+{
+#pragma unroll
+    for (int w = 0; w < EPL / 4; ++w) {
+        int a = __builtin_amdgcn_cvt_pk_fp8_f32(v[4 * w] * inv, v[4 * w + 1] * inv, 0, false);
+        a = __builtin_amdgcn_cvt_pk_fp8_f32(v[4 * w + 2] * inv, v[4 * w + 3] * inv, a, true);
+        word[w] = (u32)a;
+    }
+}
+
+template <int EPL, int LPG>
+__device__ __forceinline__ void quantize_lane_fp8(const float (&v)[EPL], int lpg_rt, u32 (&word)[EPL / 4],
+                                                  float &s)
+{
+    const float amax = group_max<LPG>(lane_absmax(v), lpg_rt);
+    float inv;
+    group_params_absmax<448>(amax, s, inv);
+    pack_lane_fp8<EPL>(v, inv, word);
+}
+
+template <int EPL>
+__device__ __forceinline__ void quantize_lane_fp8_any(const float (&v)[EPL], int lpg, float (*slot)[2],
+                                                      u32 wave, u32 lane, u32 (&word)[EPL / 4], float &s)
+{
+    float amax = group_max<0>(lane_absmax(v), lpg);
+    if (lpg > 64) {
+        float lo = -amax;
+        cross_wave_minmax(lo, amax, slot, wave, lane, (u32)lpg >> 6);
+    }
+    float inv;
+    group_params_absmax<448>(amax, s, inv);
+    pack_lane_fp8<EPL>(v, inv, word);
+}
+
+// d[e] = value of the e-th E4M3 byte of the lane's 128 bits
+__device__ __forceinline__ void decode_fp8(const u32 (&w)[4], float (&d)[16])
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], false);
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], true);
+        d[4 * k + 0] = lo.x;
+        d[4 * k + 1] = lo.y;
+        d[4 * k + 2] = hi.x;
+        d[4 * k + 3] = hi.y;
+    }
+}
+
+// acc[e] = fma(value(q_e), s, acc[e])
+__device__ __forceinline__ void accumulate_fp8(const u32 (&w)[4], float s, float (&acc)[16])
+{
+    float d[16];
+    decode_fp8(w, d);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = fmaf(d[i], s, acc[i]);
 }
 
 // signed codes -> offset binary (q + 2^(n-1)) and the matching "zero-point"
@@ -700,8 +782,8 @@ __device__ __forceinline__ void accumulate_general(const u32 (&w)[4], float s, f
 // One tile of 256*EPL elements per workgroup.  The wavefront's 64*EPL*2 input
 // bytes are fetched as coalesced 1 KB pieces straight into LDS (an image of
 // global memory) and each lane then reads its EPL contiguous values from there.
-// SYM selects the symmetric quantizer (Eq. 3-4; `zeros` is then unused).
-template <int BITS, int LPG, bool SYM>
+// CODEC selects the quantizer (`zeros` is used by kAsym only).
+template <int BITS, int LPG, int CODEC>
 __global__ FC_KERNEL_ATTRS void k_quantize(
     const uint16_t *__restrict__ x, int64_t n_elems, int lpg, int group_shift,
     uint8_t *__restrict__ codes, float *__restrict__ scales, float *__restrict__ zeros)
@@ -717,7 +799,7 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
     const rsrc_t rx = make_rsrc(x + e_tile, (n_elems - e_tile) * 2);
     const rsrc_t rc = make_rsrc(codes + e_tile * BITS / 8, (n_elems - e_tile) * BITS / 8);
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
-    const rsrc_t rz = make_rsrc(SYM ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
+    const rsrc_t rz = make_rsrc(CODEC != kAsym ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
 
 #pragma unroll
     for (int k = 0; k < kPieces; ++k)
@@ -739,7 +821,9 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
 
     u32 word[EPL * BITS / 32];
     float s, zf = 0.0f;
-    if constexpr (SYM)
+    if constexpr (CODEC == kFp8)
+        quantize_lane_fp8<EPL, LPG>(v, lpg, word, s);
+    else if constexpr (CODEC == kSym)
         quantize_lane_sym<BITS, EPL, LPG>(v, lpg, word, s);
     else
         quantize_lane<BITS, EPL, LPG>(v, lpg, word, s, zf);
@@ -748,7 +832,7 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
     if ((tid & (lpg_v - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
         store_f32(rs, gi * 4, s);
-        if constexpr (!SYM) store_f32(rz, gi * 4, zf);
+        if constexpr (CODEC == kAsym) store_f32(rz, gi * 4, zf);
     }
 }
 
@@ -891,7 +975,8 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant(
 // word and then take the fast path above with the constant "zero-point"
 // 2^(n-1), so there is nothing to check or tabulate: each lane reads its
 // group's scale of every source directly.
-template <int BITS_IN, int BITS_OUT, int NSRC, int LPG>
+// FP8 = true: the bytes are E4M3 numbers instead of signed integers (8 bit on both sides).
+template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool FP8 = false>
 __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, int64_t meta_stride,
@@ -937,15 +1022,26 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
         wait_vmem_outstanding(NSRC - 1 - j);
         u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
         lds_read_complete(a);
-        const u32 w[4] = {to_offset_binary<BITS_IN>(a[0]), to_offset_binary<BITS_IN>(a[1]),
-                          to_offset_binary<BITS_IN>(a[2]), to_offset_binary<BITS_IN>(a[3])};
-        accumulate_fast<BITS_IN>(w, sc[j], zc, acc);
+        if constexpr (FP8) {
+            const u32 w[4] = {a[0], a[1], a[2], a[3]};
+            accumulate_fp8(w, sc[j], acc);
+        } else {
+            const u32 w[4] = {to_offset_binary<BITS_IN>(a[0]), to_offset_binary<BITS_IN>(a[1]),
+                              to_offset_binary<BITS_IN>(a[2]), to_offset_binary<BITS_IN>(a[3])};
+            accumulate_fast<BITS_IN>(w, sc[j], zc, acc);
+        }
         pin_values(acc);
     }
 
     u32 word[EPL * BITS_OUT / 32];
     float s;
-    if constexpr (LPG == 0)
+    if constexpr (FP8) {
+        static_assert(!FP8 || (BITS_IN == 8 && BITS_OUT == 8), "E4M3 is an 8-bit code");
+        if constexpr (LPG == 0)
+            quantize_lane_fp8_any<EPL>(acc, lpg, slot, wave, lane, word, s);
+        else
+            quantize_lane_fp8<EPL, LPG>(acc, lpg, word, s);
+    } else if constexpr (LPG == 0)
         quantize_lane_sym_any<BITS_OUT, EPL>(acc, lpg, slot, wave, lane, word, s);
     else
         quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, lpg, word, s);
@@ -958,7 +1054,7 @@ __global__ FC_KERNEL_ATTRS void k_dequant_reduce_requant_sym(
 // Dequantize to binary16 (Algorithm 1, last step): y = half_rne((q - z) * s).
 // One tile of 256*EPL elements per workgroup; the EPL halves of a lane are laid
 // out in the wavefront's LDS image and leave as coalesced 1 KB pieces.
-template <int BITS, bool SYM>
+template <int BITS, int CODEC>
 __global__ FC_KERNEL_ATTRS void k_dequantize(
     const uint8_t *__restrict__ codes, const float *__restrict__ scales,
     const float *__restrict__ zeros, int64_t n_elems, int group_shift, uint16_t *__restrict__ y)
@@ -974,14 +1070,17 @@ __global__ FC_KERNEL_ATTRS void k_dequantize(
     const u32 gi = (tid * EPL) >> group_shift;
     const rsrc_t rc = make_rsrc(codes + e_tile * BITS / 8, (n_elems - e_tile) * BITS / 8);
     const rsrc_t rs = make_rsrc(scales + g_tile, (n_groups - g_tile) * 4);
-    const rsrc_t rz = make_rsrc(SYM ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
+    const rsrc_t rz = make_rsrc(CODEC != kAsym ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t ry = make_rsrc(y + e_tile, (n_elems - e_tile) * 2);
 
     const float s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
     const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamPolicy);
 
     float d[EPL];
-    if constexpr (SYM) {
+    if constexpr (CODEC == kFp8) {
+        const u32 w[4] = {a[0], a[1], a[2], a[3]};
+        decode_fp8(w, d);
+    } else if constexpr (CODEC == kSym) {
         const u32 w[4] = {to_offset_binary<BITS>(a[0]), to_offset_binary<BITS>(a[1]),
                           to_offset_binary<BITS>(a[2]), to_offset_binary<BITS>(a[3])};
         codes_minus_zero_fast<BITS>(w, sym_zero_const<BITS>(), d);

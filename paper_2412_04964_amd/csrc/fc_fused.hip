@@ -18,7 +18,17 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 {
     const int64_t tile = block_elems(FC_BITS_IN);
     const int64_t blocks = (a.n_elems + tile - 1) / tile;
-    if (a.zeros_in == nullptr) {
+#if FC_BITS_IN == 8 && FC_BITS_OUT == 8
+    if (a.codec == CODEC_FP8) {
+        k_dequant_reduce_requant_sym<8, 8, NSRC, LPG, true>
+            <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+                static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
+                a.n_elems, a.group / lane_elems(8), log2_int(a.group),
+                static_cast<uint8_t *>(a.codes_out), a.scales_out);
+        return hipGetLastError();
+    }
+#endif
+    if (a.codec == CODEC_SYM) {
         k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
             <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
@@ -26,6 +36,7 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
         return hipGetLastError();
     }
+    if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
         <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,

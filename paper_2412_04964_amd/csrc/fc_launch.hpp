@@ -7,17 +7,20 @@
 
 namespace fc {
 
+// Quantizer: 0 = asymmetric (Eq. 1-2), 1 = symmetric (Eq. 3-4), 2 = FP8 E4M3 (8 bit only);
+// the values match kAsym / kSym / kFp8 of the device code.  Only codec 0 uses zero-points.
+enum { CODEC_ASYM = 0, CODEC_SYM = 1, CODEC_FP8 = 2 };
+
 // n_elems = tokens*hidden (a multiple of `group`, which is a power of two in
-// [32, 16384]).  All pointers are device pointers.  zeros == nullptr selects the
-// symmetric quantizer (scales only).
-hipError_t launch_quantize(int bits, const void *x_f16, int64_t n_elems, int group,
+// [32, 16384]).  All pointers are device pointers.
+hipError_t launch_quantize(int bits, int codec, const void *x_f16, int64_t n_elems, int group,
                            void *codes, float *scales, float *zeros, hipStream_t stream);
 
-hipError_t launch_dequantize(int bits, const void *codes, const float *scales, const float *zeros,
+hipError_t launch_dequantize(int bits, int codec, const void *codes, const float *scales, const float *zeros,
                              int64_t n_elems, int group, void *y_f16, hipStream_t stream);
 
-// zeros_in == nullptr (and zeros_out == nullptr) selects the symmetric quantizer
 struct FusedArgs {
+    int codec;
     const void *codes_in;
     int64_t codes_stride;
     const float *scales_in;
@@ -44,7 +47,7 @@ hipError_t launch_fused_8_8(const FusedArgs &a, hipStream_t stream);
 inline bool is_wide_group(int bits, int group) { return group * bits / 128 > 64; }
 inline bool exceeds_tile(int bits, int group) { return group * bits / 128 > 256; }
 
-hipError_t launch_quantize_wide(int bits, const void *x_f16, int64_t n_elems, int group,
+hipError_t launch_quantize_wide(int bits, int codec, const void *x_f16, int64_t n_elems, int group,
                                 void *codes, float *scales, float *zeros, hipStream_t stream);
 hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipStream_t stream);
 

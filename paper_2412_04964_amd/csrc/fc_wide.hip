@@ -34,7 +34,7 @@ __device__ __forceinline__ void block_minmax(float &mn, float &mx, float (*slot)
 }
 
 // FinegrainedQuantize of binary16 input, one group per workgroup.
-template <int BITS, int P, bool SYM>
+template <int BITS, int P, int CODEC>
 __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
     const uint16_t *__restrict__ x, int group, uint8_t *__restrict__ codes,
     float *__restrict__ scales, float *__restrict__ zeros)
@@ -85,14 +85,18 @@ __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
     block_minmax(mn, mx, slot, wave, lane);
 
     float s, inv, zf = 0.0f;
-    if constexpr (SYM)
+    if constexpr (CODEC == kFp8)
+        group_params_absmax<448>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);
+    else if constexpr (CODEC == kSym)
         group_params_sym<BITS>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);   // max|x| = max(|min|, |max|)
     else
         group_params<BITS>(mn, mx, s, inv, zf);
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         u32 word[EPL * BITS / 32];
-        if constexpr (SYM)
+        if constexpr (CODEC == kFp8)
+            pack_lane_fp8<EPL>(v[p], inv, word);
+        else if constexpr (CODEC == kSym)
             pack_lane_sym<BITS, EPL>(v[p], inv, word);
         else
             pack_lane<BITS, EPL>(v[p], inv, zf, mx, word);
@@ -101,12 +105,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
     }
     if (tid == 0) {
         scales[blockIdx.x] = s;
-        if constexpr (!SYM) zeros[blockIdx.x] = zf;
+        if constexpr (CODEC == kAsym) zeros[blockIdx.x] = zf;
     }
 }
 
 // Dequantize x n_src, ReduceSum, FinegrainedQuantize, one group per workgroup.
-template <int BITS_IN, int BITS_OUT, int P, bool SYM>
+template <int BITS_IN, int BITS_OUT, int P, int CODEC>
 __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, const float *__restrict__ zeros_in, int64_t meta_stride,
@@ -152,7 +156,13 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
             if (j0 + d < n_src) {
                 const int j = j0 + d;
                 const float s = scales_in[(int64_t)j * meta_stride + g_idx];
-                if constexpr (SYM) {
+                if constexpr (CODEC == kFp8) {
+#pragma unroll
+                    for (int p = 0; p < P; ++p) {
+                        const u32 w[4] = {src[d][p][0], src[d][p][1], src[d][p][2], src[d][p][3]};
+                        accumulate_fp8(w, s, acc[p]);
+                    }
+                } else if constexpr (CODEC == kSym) {
                     const ZeroConst zc = sym_zero_const<BITS_IN>();
 #pragma unroll
                     for (int p = 0; p < P; ++p) {
@@ -199,7 +209,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
     block_minmax(mn, mx, slot, wave, lane);
 
     float s, inv, zf = 0.0f;
-    if constexpr (SYM)
+    if constexpr (CODEC == kFp8)
+        group_params_absmax<448>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);
+    else if constexpr (CODEC == kSym)
         group_params_sym<BITS_OUT>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);
     else
         group_params<BITS_OUT>(mn, mx, s, inv, zf);
@@ -209,7 +221,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         u32 word[EPL * BITS_OUT / 32];
-        if constexpr (SYM)
+        if constexpr (CODEC == kFp8)
+            pack_lane_fp8<EPL>(acc[p], inv, word);
+        else if constexpr (CODEC == kSym)
             pack_lane_sym<BITS_OUT, EPL>(acc[p], inv, word);
         else
             pack_lane<BITS_OUT, EPL>(acc[p], inv, zf, mx, word);
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
     }
     if (tid == 0) {
         scales_out[g_idx] = s;
-        if constexpr (!SYM) zeros_out[g_idx] = zf;
+        if constexpr (CODEC == kAsym) zeros_out[g_idx] = zf;
     }
 }
 
@@ -244,18 +258,18 @@ WideShape wide_shape(int bits, int group)
     return w;
 }
 
-template <int BITS, bool SYM>
+template <int BITS, int CODEC>
 hipError_t quantize_wide_bits(const uint16_t *x, int64_t n_elems, int group, uint8_t *c,
                               float *scales, float *zeros, hipStream_t stream)
 {
     const WideShape w = wide_shape(BITS, group);
     const dim3 grid((unsigned)(n_elems / group)), block(w.threads);
     switch (w.p) {
-    case 1: k_quantize_wide<BITS, 1, SYM><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
-    case 2: k_quantize_wide<BITS, 2, SYM><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
+    case 1: k_quantize_wide<BITS, 1, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
+    case 2: k_quantize_wide<BITS, 2, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
     case 4:
         if constexpr (BITS == 8) {
-            k_quantize_wide<BITS, 4, SYM><<<grid, block, 0, stream>>>(x, group, c, scales, zeros);
+            k_quantize_wide<BITS, 4, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros);
             break;
         }
         [[fallthrough]];
@@ -264,7 +278,7 @@ hipError_t quantize_wide_bits(const uint16_t *x, int64_t n_elems, int group, uin
     return hipGetLastError();
 }
 
-template <int BI, int BO, bool SYM>
+template <int BI, int BO, int CODEC>
 hipError_t fused_wide_bits(const FusedArgs &a, hipStream_t stream)
 {
     const WideShape w = wide_shape(BI, a.group);
@@ -272,7 +286,7 @@ hipError_t fused_wide_bits(const FusedArgs &a, hipStream_t stream)
     const uint8_t *ci = static_cast<const uint8_t *>(a.codes_in);
     uint8_t *co = static_cast<uint8_t *>(a.codes_out);
 #define FC_WIDE_LAUNCH(PP)                                                                               \
-    k_dequant_reduce_requant_wide<BI, BO, PP, SYM><<<grid, block, 0, stream>>>(                          \
+    k_dequant_reduce_requant_wide<BI, BO, PP, CODEC><<<grid, block, 0, stream>>>(                          \
         ci, a.codes_stride, a.scales_in, a.zeros_in, a.meta_stride, a.n_src, a.group, co, a.scales_out, \
         a.zeros_out)
     switch (w.p) {
@@ -292,28 +306,33 @@ hipError_t fused_wide_bits(const FusedArgs &a, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_quantize_wide(int bits, const void *x_f16, int64_t n_elems, int group,
+hipError_t launch_quantize_wide(int bits, int codec, const void *x_f16, int64_t n_elems, int group,
                                 void *codes, float *scales, float *zeros, hipStream_t stream)
 {
     const uint16_t *x = static_cast<const uint16_t *>(x_f16);
     uint8_t *c = static_cast<uint8_t *>(codes);
+    if (codec == CODEC_FP8)
+        return bits == 8 ? quantize_wide_bits<8, kFp8>(x, n_elems, group, c, scales, nullptr, stream)
+                         : hipErrorInvalidValue;
     if (bits == 4)
-        return zeros ? quantize_wide_bits<4, false>(x, n_elems, group, c, scales, zeros, stream)
-                     : quantize_wide_bits<4, true>(x, n_elems, group, c, scales, nullptr, stream);
-    return zeros ? quantize_wide_bits<8, false>(x, n_elems, group, c, scales, zeros, stream)
-                 : quantize_wide_bits<8, true>(x, n_elems, group, c, scales, nullptr, stream);
+        return codec == CODEC_ASYM ? quantize_wide_bits<4, kAsym>(x, n_elems, group, c, scales, zeros, stream)
+                                   : quantize_wide_bits<4, kSym>(x, n_elems, group, c, scales, nullptr, stream);
+    return codec == CODEC_ASYM ? quantize_wide_bits<8, kAsym>(x, n_elems, group, c, scales, zeros, stream)
+                               : quantize_wide_bits<8, kSym>(x, n_elems, group, c, scales, nullptr, stream);
 }
 
 hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipStream_t stream)
 {
-    const bool sym = a.zeros_in == nullptr;
+    if (a.codec == CODEC_FP8)
+        return (bits_in == 8 && bits_out == 8) ? fused_wide_bits<8, 8, kFp8>(a, stream) : hipErrorInvalidValue;
+    const bool sym = a.codec == CODEC_SYM;
     if (bits_in == 4 && bits_out == 4)
-        return sym ? fused_wide_bits<4, 4, true>(a, stream) : fused_wide_bits<4, 4, false>(a, stream);
+        return sym ? fused_wide_bits<4, 4, kSym>(a, stream) : fused_wide_bits<4, 4, kAsym>(a, stream);
     if (bits_in == 4)
-        return sym ? fused_wide_bits<4, 8, true>(a, stream) : fused_wide_bits<4, 8, false>(a, stream);
+        return sym ? fused_wide_bits<4, 8, kSym>(a, stream) : fused_wide_bits<4, 8, kAsym>(a, stream);
     if (bits_out == 4)
-        return sym ? fused_wide_bits<8, 4, true>(a, stream) : fused_wide_bits<8, 4, false>(a, stream);
-    return sym ? fused_wide_bits<8, 8, true>(a, stream) : fused_wide_bits<8, 8, false>(a, stream);
+        return sym ? fused_wide_bits<8, 4, kSym>(a, stream) : fused_wide_bits<8, 4, kAsym>(a, stream);
+    return sym ? fused_wide_bits<8, 8, kSym>(a, stream) : fused_wide_bits<8, 8, kAsym>(a, stream);
 }
 
 }  // namespace fc

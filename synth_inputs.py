@@ -30,7 +30,8 @@ class Workload:
     outlier_frac: float = 0.01
     outlier_gain: float = 20.0
     seed: int = 0
-    quantizer: str = "asym"   # "asym": Eq. 1-2 (scale + zero-point), "sym": Eq. 3-4 (scale only)
+    quantizer: str = "asym"   # "asym": Eq. 1-2 (scale + zero-point), "sym": Eq. 3-4 (scale only),
+                              # "fp8": E4M3 bytes with a per-group scale (the paper's FP8_Sym rows)
 
     @property
     def elements(self) -> int:
@@ -54,6 +55,8 @@ WORKLOADS = {
     "llama3_70b_prefill_int6": Workload("llama3_70b_prefill_int6", 4, 8192, 8192, 4, 8, 128),
     "llama3_70b_prefill_sym": Workload("llama3_70b_prefill_sym", 4, 8192, 8192, 4, 4, 128, quantizer="sym"),
     "llama3_70b_prefill_per_token": Workload("llama3_70b_prefill_per_token", 4, 8192, 8192, 4, 4, 8192),
+    "llama3_70b_prefill_fp8": Workload("llama3_70b_prefill_fp8", 4, 8192, 8192, 8, 8, 128, quantizer="fp8"),
+    "llama3_8b_prefill_fp8": Workload("llama3_8b_prefill_fp8", 4, 8192, 4096, 8, 8, 128, quantizer="fp8"),
     "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
 }
 
