@@ -45,6 +45,13 @@ def sweep(x, groups, precisions=PRECISIONS):
                 rows.append({"precision": label, "quantizer": quantizer, "group": g, "mse": mse,
                              "snr_db": float(10.0 * torch.log10(torch.tensor(power / mse))) if mse > 0
                              else float("inf")})
+    for g in groups:                                   # the paper's FP8_Sym rows
+        if x.shape[2] % g:
+            continue
+        err = fc.allreduce_sim_fp8(x, g).float() - exact
+        mse = float((err * err).mean())
+        rows.append({"precision": "FP8", "quantizer": "sym", "group": g, "mse": mse,
+                     "snr_db": float(10.0 * torch.log10(torch.tensor(power / mse))) if mse > 0 else float("inf")})
     return rows
 
 
@@ -71,10 +78,11 @@ def main():
     print("all-reduce quantization error, N=%d partials of %d x %d (N(0,1), 1%% outlier channels x20)"
           % (a.n_src, a.tokens, a.hidden))
     print("%-6s %-5s " % ("prec", "quant") + " ".join("%10s" % ("g=%d" % g) for g in groups))
-    for label in PRECISIONS:
+    for label in ("FP8",) + tuple(PRECISIONS):
         for q in ("asym", "sym"):
             r = {row["group"]: row for row in rows if row["precision"] == label and row["quantizer"] == q}
-            print("%-6s %-5s " % (label, q) + " ".join("%10.3e" % r[g]["mse"] for g in groups))
+            if r:
+                print("%-6s %-5s " % (label, q) + " ".join("%10.3e" % r[g]["mse"] for g in groups))
 
 
 if __name__ == "__main__":
