@@ -80,6 +80,13 @@ def lib() -> ctypes.CDLL:
         L.fc_ref_dequant_reduce_fp8_f32.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp]
         L.fc_ref_dequant_reduce_requant_fp8.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp, vp]
         L.fc_ref_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp]
+        L.fc_ref_hadamard_f32.argtypes = [vp, i64]
+        L.fc_ref_quantize_rot.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
+        L.fc_ref_dequantize_rot.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp]
+        L.fc_ref_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp]
+        for name in ("fc_ref_hadamard_f32", "fc_ref_quantize_rot", "fc_ref_dequantize_rot",
+                     "fc_ref_allreduce_sim_rot"):
+            getattr(L, name).restype = i32
         for name in ("fc_ref_quantize_fp8_f32", "fc_ref_quantize_fp8", "fc_ref_dequantize_fp8_f32",
                      "fc_ref_dequantize_fp8", "fc_ref_dequant_reduce_fp8_f32",
                      "fc_ref_dequant_reduce_requant_fp8", "fc_ref_allreduce_sim_fp8"):
@@ -384,4 +391,53 @@ def allreduce_sim_fp8(x_f16, group: int):
     n, t, h = x.shape
     y = np.zeros((t, h), np.uint16)
     _chk(lib().fc_ref_allreduce_sim_fp8(_p(x), n, t, h, group, _p(y)), "allreduce_sim_fp8")
+    return y.view(np.float16)
+
+
+# --------------------------------------------------------------------------- #
+# Hadamard rotation around the quantized all-reduce (quantizer: 0 asym, 1 sym, 2 fp8)
+# --------------------------------------------------------------------------- #
+
+ASYM, SYM, FP8 = 0, 1, 2
+
+
+def hadamard_f32(x):
+    """unnormalised Walsh-Hadamard transform (natural order) of the last axis, fp32 butterflies."""
+    x = np.array(x, dtype=np.float32, order="C")
+    n = x.shape[-1]
+    flat = x.reshape(-1, n)
+    for r in range(flat.shape[0]):
+        row = np.ascontiguousarray(flat[r])
+        _chk(lib().fc_ref_hadamard_f32(_p(row), n), "hadamard_f32")
+        flat[r] = row
+    return flat.reshape(x.shape)
+
+
+def quantize_rot(x_f16, group: int, bits: int, quantizer: int = ASYM):
+    """-> (codes, scales, zeros); zeros is all-zero and meaningless unless quantizer == ASYM."""
+    x = _as_u16(x_f16)
+    t, h = x.shape
+    _chk(0 if (h % group == 0 and bits in (4, 8)) else -1, "quantize_rot")
+    c, s, z = _alloc_q(t, h, group, bits)
+    _chk(lib().fc_ref_quantize_rot(_p(x), t, h, group, bits, quantizer, _p(c), _p(s), _p(z)), "quantize_rot")
+    return c, s, z
+
+
+def dequantize_rot(codes, scales, zeros, hidden: int, group: int, bits: int, quantizer: int = ASYM):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    zeros = np.ascontiguousarray(zeros if zeros is not None else np.zeros_like(scales), np.float32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.uint16)
+    _chk(lib().fc_ref_dequantize_rot(_p(codes), _p(scales), _p(zeros), t, hidden, group, bits, quantizer,
+                                     _p(y)), "dequantize_rot")
+    return y.view(np.float16)
+
+
+def allreduce_sim_rot(x_f16, group: int, bits_rs: int, bits_ag: int, quantizer: int = ASYM):
+    x = _as_u16(x_f16)
+    n, t, h = x.shape
+    y = np.zeros((t, h), np.uint16)
+    _chk(lib().fc_ref_allreduce_sim_rot(_p(x), n, t, h, group, bits_rs, bits_ag, quantizer, _p(y)),
+         "allreduce_sim_rot")
     return y.view(np.float16)

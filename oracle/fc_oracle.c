@@ -59,6 +59,23 @@
  *       values, as with the clamps of Eq. 4);
  *   F4  Dequantize is x^ = value(q) * s; the N-way sum is
  *       acc = fma(value(q_j), s_j, acc) from +0.
+ * Rotation variant (Section 4, "Naive vs. Rotation-based Quantization": the
+ * Hadamard transform of QuaRot applied around the quantized all-reduce; the paper
+ * gives no formula): the fc_ref_*_rot functions, with
+ *   H1  the transform is the Walsh-Hadamard transform in natural (Sylvester)
+ *       order over the whole hidden dimension of one token, hidden a power of
+ *       two; every partial is rotated before the first quantization, the sum of
+ *       rotated partials is the rotated sum, and the inverse is applied once
+ *       after the last Dequantize;
+ *   H2  it is evaluated in fp32 as log2(hidden) butterfly stages with spans
+ *       1, 2, 4, ..., hidden/2 in that order, each butterfly (a, b) -> (a+b, a-b);
+ *   H3  the forward transform is scaled by 2^-ceil(n/2) and the inverse by
+ *       2^-floor(n/2), n = log2(hidden): exact scalings whose product is 1/hidden
+ *       (the orthonormal transform up to an exact power of two, to which the
+ *       group quantizers are invariant);
+ *   H4  the rotated values go into the quantizer in fp32 (no rounding to
+ *       binary16 in between); the result is binary16(RNE) of the inverse transform
+ *       of the dequantized fp32 values.
  * Domain: finite inputs.  NaN / Inf inputs: parity unpinned.
  *
  * Build: cc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
@@ -693,5 +710,135 @@ int fc_ref_allreduce_sim_fp8(const uint16_t *x_f16, int n_src, int64_t tokens, i
     if (rc == FC_REF_OK)
         rc = fc_ref_dequantize_fp8(c2, s2, tokens, hidden, group, y_f16);
     free(c1); free(s1); free(c2); free(s2);
+    return rc;
+}
+
+/* ======================================================================== */
+/* Hadamard rotation around the quantized all-reduce -- readings H1-H4.      */
+/* ======================================================================== */
+
+#define FC_REF_ASYM 0
+#define FC_REF_SYM 1
+#define FC_REF_FP8 2
+
+static int log2_exact(int64_t v)
+{
+    int n = 0;
+    while (((int64_t)1 << n) < v) ++n;
+    return (((int64_t)1 << n) == v) ? n : -1;
+}
+
+/* In-place unnormalised Walsh-Hadamard transform of n = 2^k fp32 values (H2). */
+int fc_ref_hadamard_f32(float *x, int64_t n)
+{
+    if (n < 1 || log2_exact(n) < 0 || !x) return FC_REF_BAD_ARG;
+    for (int64_t span = 1; span < n; span *= 2)
+        for (int64_t base = 0; base < n; base += 2 * span)
+            for (int64_t i = base; i < base + span; ++i) {
+                const float a = x[i], b = x[i + span];
+                x[i] = a + b;
+                x[i + span] = a - b;
+            }
+    return FC_REF_OK;
+}
+
+static int quantize_any_f32(int quantizer, const float *x, int64_t tokens, int64_t hidden, int group,
+                            int bits, uint8_t *codes, float *scales, float *zeros)
+{
+    if (quantizer == FC_REF_ASYM) return fc_ref_quantize_f32(x, tokens, hidden, group, bits, codes, scales, zeros);
+    if (quantizer == FC_REF_SYM) return fc_ref_quantize_sym_f32(x, tokens, hidden, group, bits, codes, scales);
+    if (quantizer == FC_REF_FP8 && bits == 8) return fc_ref_quantize_fp8_f32(x, tokens, hidden, group, codes, scales);
+    return FC_REF_BAD_ARG;
+}
+
+static int dequantize_any_f32(int quantizer, const uint8_t *codes, const float *scales, const float *zeros,
+                              int64_t tokens, int64_t hidden, int group, int bits, float *y)
+{
+    if (quantizer == FC_REF_ASYM) return fc_ref_dequantize_f32(codes, scales, zeros, tokens, hidden, group, bits, y);
+    if (quantizer == FC_REF_SYM) return fc_ref_dequantize_sym_f32(codes, scales, tokens, hidden, group, bits, y);
+    if (quantizer == FC_REF_FP8 && bits == 8) return fc_ref_dequantize_fp8_f32(codes, scales, tokens, hidden, group, y);
+    return FC_REF_BAD_ARG;
+}
+
+/* rotate each token row (H1-H3, forward scaling), then FinegrainedQuantize in fp32 (H4) */
+int fc_ref_quantize_rot(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                        int quantizer, uint8_t *codes, float *scales, float *zeros)
+{
+    const int n = log2_exact(hidden);
+    if (!check_shape(tokens, hidden, group, bits) || n < 0) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x_f16 || !codes || !scales) return FC_REF_BAD_ARG;
+    float *xf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!xf) return FC_REF_NO_MEM;
+    const float fwd = ldexpf(1.0f, -((n + 1) / 2));          /* 2^-ceil(n/2) */
+    for (int64_t t = 0; t < tokens; ++t) {
+        float *row = xf + t * hidden;
+        for (int64_t h = 0; h < hidden; ++h) row[h] = fc_ref_half_to_float(x_f16[t * hidden + h]);
+        fc_ref_hadamard_f32(row, hidden);
+        for (int64_t h = 0; h < hidden; ++h) row[h] *= fwd;
+    }
+    const int rc = quantize_any_f32(quantizer, xf, tokens, hidden, group, bits, codes, scales, zeros);
+    free(xf);
+    return rc;
+}
+
+/* Dequantize in fp32, rotate back (inverse scaling), round to binary16 (H4) */
+int fc_ref_dequantize_rot(const uint8_t *codes, const float *scales, const float *zeros,
+                          int64_t tokens, int64_t hidden, int group, int bits, int quantizer,
+                          uint16_t *y_f16)
+{
+    const int n = log2_exact(hidden);
+    if (!check_shape(tokens, hidden, group, bits) || n < 0) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !scales || !y_f16) return FC_REF_BAD_ARG;
+    float *yf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!yf) return FC_REF_NO_MEM;
+    int rc = dequantize_any_f32(quantizer, codes, scales, zeros, tokens, hidden, group, bits, yf);
+    const float inv = ldexpf(1.0f, -(n / 2));                /* 2^-floor(n/2) */
+    for (int64_t t = 0; rc == FC_REF_OK && t < tokens; ++t) {
+        float *row = yf + t * hidden;
+        fc_ref_hadamard_f32(row, hidden);
+        for (int64_t h = 0; h < hidden; ++h) y_f16[t * hidden + h] = fc_ref_float_to_half(row[h] * inv);
+    }
+    free(yf);
+    return rc;
+}
+
+/* Algorithm 1 with the rotation around it: rotate+quantize each partial, the unchanged
+   Dequantize-ReduceSum-FinegrainedQuantize step, dequantize+rotate back. */
+int fc_ref_allreduce_sim_rot(const uint16_t *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                             int group, int bits_rs, int bits_ag, int quantizer, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits_rs) || !check_shape(tokens, hidden, group, bits_ag)
+        || n_src < 1 || log2_exact(hidden) < 0)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    const int64_t m = tokens * hidden, ng = m / group;
+    const int64_t cb_rs = m * bits_rs / 8, cb_ag = m * bits_ag / 8;
+    uint8_t *c1 = (uint8_t *)malloc((size_t)(cb_rs * n_src));
+    float *s1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    float *z1 = (float *)malloc(sizeof(float) * (size_t)(ng * n_src));
+    uint8_t *c2 = (uint8_t *)malloc((size_t)cb_ag);
+    float *s2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    float *z2 = (float *)malloc(sizeof(float) * (size_t)ng);
+    int rc = (c1 && s1 && z1 && c2 && s2 && z2) ? FC_REF_OK : FC_REF_NO_MEM;
+    for (int j = 0; rc == FC_REF_OK && j < n_src; ++j)
+        rc = fc_ref_quantize_rot(x_f16 + (int64_t)j * m, tokens, hidden, group, bits_rs, quantizer,
+                                 c1 + (int64_t)j * cb_rs, s1 + (int64_t)j * ng, z1 + (int64_t)j * ng);
+    if (rc == FC_REF_OK) {
+        if (quantizer == FC_REF_ASYM)
+            rc = fc_ref_dequant_reduce_requant(c1, cb_rs, s1, z1, ng, n_src, tokens, hidden, group,
+                                               bits_rs, bits_ag, c2, s2, z2);
+        else if (quantizer == FC_REF_SYM)
+            rc = fc_ref_dequant_reduce_requant_sym(c1, cb_rs, s1, ng, n_src, tokens, hidden, group,
+                                                   bits_rs, bits_ag, c2, s2);
+        else if (bits_rs == 8 && bits_ag == 8)
+            rc = fc_ref_dequant_reduce_requant_fp8(c1, cb_rs, s1, ng, n_src, tokens, hidden, group, c2, s2);
+        else
+            rc = FC_REF_BAD_ARG;
+    }
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequantize_rot(c2, s2, z2, tokens, hidden, group, bits_ag, quantizer, y_f16);
+    free(c1); free(s1); free(z1); free(c2); free(s2); free(z2);
     return rc;
 }
