@@ -155,9 +155,13 @@ def main():
 
     sym, fp8 = w.quantizer == "sym", w.quantizer == "fp8"
 
+    qz = {"asym": fc.QUANTIZER_ASYM, "sym": fc.QUANTIZER_SYM, "fp8": fc.QUANTIZER_FP8}[w.quantizer]
+
     def stage_quantize(k):
         for j in range(N):
-            if fp8:
+            if w.rotate:
+                fc.quantize_rot(X[k][j], g, w.bits_in, qz, out=(C1[k][j], S1[k][j], Z1[k][j]))
+            elif fp8:
                 fc.quantize_fp8(X[k][j], g, out=(C1[k][j], S1[k][j]))
             elif sym:
                 fc.quantize_sym(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j]))
@@ -174,7 +178,9 @@ def main():
                                       out=(C2[k], S2[k], Z2[k]))
 
     def stage_dequantize(k):
-        if fp8:
+        if w.rotate:
+            fc.dequantize_rot(C2[k], S2[k], Z2[k], H, g, w.bits_out, qz, out=Y[k])
+        elif fp8:
             fc.dequantize_fp8(C2[k], S2[k], H, g, out=Y[k])
         elif sym:
             fc.dequantize_sym(C2[k], S2[k], H, g, w.bits_out, out=Y[k])
@@ -245,7 +251,8 @@ def main():
                         "channels x%g, %s, group %d"
                         % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain,
                            "FP8 E4M3 -> FP8 E4M3 symmetric" if fp8 else
-                           "INT%d->INT%d %s" % (w.bits_in, w.bits_out, "symmetric" if sym else "asymmetric"), g),
+                           "INT%d->INT%d %s" % (w.bits_in, w.bits_out, "symmetric" if sym else "asymmetric"), g)
+                        + (", Hadamard rotation fused into quantize / dequantize" if w.rotate else ""),
             "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
             "volumes_per_step": B,
             "stage_order": "volume-major (dependent)" if a.dependent else "stage-major over the batch",

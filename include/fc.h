@@ -196,6 +196,36 @@ FC_API int fc_dequantize_fp8(const void *codes, const float *scales,
 FC_API int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, int64_t hidden, int group,
                                 void *y_f16, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Rotation variant (paper Section 4, "Naive vs. Rotation-based Quantization": the Hadamard
+ * transform of QuaRot around the quantized all-reduce).  Every partial is rotated before
+ * the first quantization; the rotation is linear, so the unchanged
+ * fc_dequant_reduce_requant* step sums rotated partials; the inverse rotation follows the
+ * last Dequantize.  `quantizer` selects the code (FC_QUANTIZER_*; FP8 needs bits == 8;
+ * zeros may be NULL unless FC_QUANTIZER_ASYM).  hidden must be 2048, 4096 or 8192; other
+ * rules as above.  Results are bit-identical to:
+ *     r = WHT(x) * 2^-ceil(n/2),  n = log2(hidden)      (fc_quantize_rot, then the quantizer on r in fp32)
+ *     y = binary16(WHT(x^) * 2^-floor(n/2))              (fc_dequantize_rot on the dequantized fp32 x^)
+ * where WHT is the natural-order Walsh-Hadamard transform over the hidden dimension of one
+ * token, evaluated in fp32 as butterfly stages (a, b) -> (a + b, a - b) with spans
+ * 1, 2, 4, ..., hidden/2 in that order.
+ */
+#define FC_QUANTIZER_ASYM 0   /* Eq. 1-2 */
+#define FC_QUANTIZER_SYM 1    /* Eq. 3-4 */
+#define FC_QUANTIZER_FP8 2    /* E4M3 bytes */
+
+FC_API int fc_quantize_rot(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                           int quantizer, void *codes, float *scales, float *zeros, void *hip_stream);
+
+FC_API int fc_dequantize_rot(const void *codes, const float *scales, const float *zeros,
+                             int64_t tokens, int64_t hidden, int group, int bits, int quantizer,
+                             void *y_f16, void *hip_stream);
+
+/* Algorithm 1 with the rotation around it; workspace as for fc_allreduce_sim. */
+FC_API int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                                int group, int bits_rs, int bits_ag, int quantizer, void *y_f16,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);
 

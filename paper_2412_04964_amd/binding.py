@@ -14,6 +14,7 @@ _LIB_PATH = os.environ.get("FC_LIBRARY") or os.path.join(_HERE, "libfc.so")
 _lib = None
 
 FC_MAX_SRC = 8
+QUANTIZER_ASYM, QUANTIZER_SYM, QUANTIZER_FP8 = 0, 1, 2
 
 
 class FcError(RuntimeError):
@@ -67,6 +68,12 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize_fp8.restype = i32
         L.fc_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim_fp8.restype = i32
+        L.fc_quantize_rot.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.fc_quantize_rot.restype = i32
+        L.fc_dequantize_rot.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp]
+        L.fc_dequantize_rot.restype = i32
+        L.fc_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.fc_allreduce_sim_rot.restype = i32
         L.fc_strerror.argtypes = [i32]
         L.fc_strerror.restype = ctypes.c_char_p
         L.fc_last_hip_error.argtypes = []
@@ -352,4 +359,69 @@ def allreduce_sim_fp8(x, group: int, out=None, workspace=None):
     _dev(y, torch.float16, "y")
     _check(lib().fc_allreduce_sim_fp8(x.data_ptr(), n, t, h, group, y.data_ptr(), workspace.data_ptr(),
                                       workspace.numel(), _stream()), "fc_allreduce_sim_fp8")
+    return y
+
+
+# ---- Hadamard rotation fused into the first quantization and the last dequantization ----
+
+def quantize_rot(x, group: int, bits: int, quantizer: int = QUANTIZER_ASYM, out=None):
+    """fc_quantize_rot.  x: float16 [tokens, hidden] -> (codes, scales, zeros); zeros is None
+    unless quantizer == QUANTIZER_ASYM."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    t, h = x.shape
+    asym = quantizer == QUANTIZER_ASYM
+    if out is None:
+        if bits not in (4, 8) or group <= 0 or h % group:
+            _check(lib().fc_quantize_rot(None, t, h, group, bits, quantizer, None, None, None, None),
+                   "fc_quantize_rot")
+        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
+        zeros = torch.empty_like(scales) if asym else None
+    else:
+        codes, scales, zeros = out
+        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+        if asym:
+            _dev(zeros, torch.float32, "zeros")
+    _check(lib().fc_quantize_rot(x.data_ptr(), t, h, group, bits, quantizer, codes.data_ptr(),
+                                 scales.data_ptr(), zeros.data_ptr() if asym else None, _stream()),
+           "fc_quantize_rot")
+    return codes, scales, (zeros if asym else None)
+
+
+def dequantize_rot(codes, scales, zeros, hidden: int, group: int, bits: int,
+                   quantizer: int = QUANTIZER_ASYM, out=None):
+    """fc_dequantize_rot -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    asym = quantizer == QUANTIZER_ASYM
+    if asym:
+        _dev(zeros, torch.float32, "zeros")
+    t = codes.shape[0]
+    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_dequantize_rot(codes.data_ptr(), scales.data_ptr(), zeros.data_ptr() if asym else None,
+                                   t, hidden, group, bits, quantizer, y.data_ptr(), _stream()),
+           "fc_dequantize_rot")
+    return y
+
+
+def allreduce_sim_rot(x, group: int, bits_rs: int, bits_ag: int, quantizer: int = QUANTIZER_ASYM,
+                      out=None, workspace=None):
+    """fc_allreduce_sim_rot.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    n, t, h = x.shape
+    need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
+    if need == 0 and t != 0:
+        _check(lib().fc_allreduce_sim_rot(None, n, t, h, group, bits_rs, bits_ag, quantizer, None, None, 0,
+                                          None), "fc_allreduce_sim_rot")
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_allreduce_sim_rot(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, quantizer,
+                                      y.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
+           "fc_allreduce_sim_rot")
     return y

@@ -31,7 +31,8 @@ FLAGS = [
 ]
 
 # (source, object suffix, extra defines)
-UNITS = [("fc_api.hip", "api", []), ("fc_codec.hip", "codec", []), ("fc_wide.hip", "wide", [])]
+UNITS = [("fc_api.hip", "api", []), ("fc_codec.hip", "codec", []), ("fc_wide.hip", "wide", []),
+         ("fc_rot.hip", "rot", [])]
 for _bi in (4, 8):
     for _bo in (4, 8):
         UNITS.append(("fc_fused.hip", "fused_%d_%d" % (_bi, _bo),

@@ -188,6 +188,49 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
                            bits_ag, y_f16, hip_stream);
 }
 
+bool rot_hidden_ok(int64_t hidden) { return hidden == 2048 || hidden == 4096 || hidden == 8192; }
+
+int check_quantizer(int quantizer, int bits)
+{
+    if (quantizer != fc::CODEC_ASYM && quantizer != fc::CODEC_SYM && quantizer != fc::CODEC_FP8) return FC_ERR_SHAPE;
+    if (quantizer == fc::CODEC_FP8 && bits != 8) return FC_ERR_BITS;
+    return FC_OK;
+}
+
+int quantize_rot_impl(int codec, const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                      void *codes, float *scales, float *zeros, void *hip_stream)
+{
+    const bool sym = codec != fc::CODEC_ASYM;
+    int64_t n = 0;
+    int rc = check_shape(tokens, hidden, group, bits, &n);
+    if (rc != FC_OK) return rc;
+    if ((rc = check_quantizer(codec, bits)) != FC_OK) return rc;
+    if (!rot_hidden_ok(hidden) || tokens > 0x7FFFFFFF) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!x_f16 || !codes || !scales || (!sym && !zeros)) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(codes) || !aligned16(scales) || (!sym && !aligned16(zeros)))
+        return FC_ERR_ALIGN;
+    return hip_result(fc::launch_quantize_rot(bits, codec, x_f16, tokens, (int)hidden, group, codes, scales,
+                                              sym ? nullptr : zeros, static_cast<hipStream_t>(hip_stream)));
+}
+
+int dequantize_rot_impl(int codec, const void *codes, const float *scales, const float *zeros,
+                        int64_t tokens, int64_t hidden, int group, int bits, void *y_f16, void *hip_stream)
+{
+    const bool sym = codec != fc::CODEC_ASYM;
+    int64_t n = 0;
+    int rc = check_shape(tokens, hidden, group, bits, &n);
+    if (rc != FC_OK) return rc;
+    if ((rc = check_quantizer(codec, bits)) != FC_OK) return rc;
+    if (!rot_hidden_ok(hidden) || tokens > 0x7FFFFFFF) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!codes || !scales || !y_f16 || (!sym && !zeros)) return FC_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(y_f16) || (!sym && !aligned16(zeros)))
+        return FC_ERR_ALIGN;
+    return hip_result(fc::launch_dequantize_rot(bits, codec, codes, scales, sym ? nullptr : zeros, tokens,
+                                                (int)hidden, group, y_f16, static_cast<hipStream_t>(hip_stream)));
+}
+
 }  // namespace
 
 extern "C" {
@@ -295,6 +338,58 @@ int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, int64_t h
 {
     return allreduce_sim_impl(fc::CODEC_FP8, x_f16, n_src, tokens, hidden, group, 8, 8, y_f16,
                               workspace, workspace_bytes, hip_stream);
+}
+
+int fc_quantize_rot(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                    int quantizer, void *codes, float *scales, float *zeros, void *hip_stream)
+{
+    return quantize_rot_impl(quantizer, x_f16, tokens, hidden, group, bits, codes, scales, zeros, hip_stream);
+}
+
+int fc_dequantize_rot(const void *codes, const float *scales, const float *zeros,
+                      int64_t tokens, int64_t hidden, int group, int bits, int quantizer,
+                      void *y_f16, void *hip_stream)
+{
+    return dequantize_rot_impl(quantizer, codes, scales, zeros, tokens, hidden, group, bits, y_f16, hip_stream);
+}
+
+int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                         int group, int bits_rs, int bits_ag, int quantizer, void *y_f16,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int64_t n = 0;
+    int rc = check_shape(tokens, hidden, group, bits_rs, &n);
+    if (rc != FC_OK) return rc;
+    if (bits_ag != 4 && bits_ag != 8) return FC_ERR_BITS;
+    if ((rc = check_quantizer(quantizer, bits_rs)) != FC_OK) return rc;
+    if ((rc = check_quantizer(quantizer, bits_ag)) != FC_OK) return rc;
+    if (n_src < 1 || n_src > FC_MAX_SRC || !rot_hidden_ok(hidden)) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!x_f16 || !y_f16) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return FC_ERR_ALIGN;
+    const SimLayout L = sim_layout(n_src, n, group, bits_rs, bits_ag);
+    if (!workspace || workspace_bytes < L.total) return FC_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FC_ERR_ALIGN;
+
+    char *ws = static_cast<char *>(workspace);
+    const char *x = static_cast<const char *>(x_f16);
+    for (int j = 0; j < n_src; ++j) {
+        rc = quantize_rot_impl(quantizer, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
+                               ws + L.off_codes1 + (size_t)j * L.codes_rs,
+                               reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
+                               reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta), hip_stream);
+        if (rc != FC_OK) return rc;
+    }
+    rc = fused_impl(quantizer, ws + L.off_codes1, (int64_t)L.codes_rs,
+                    reinterpret_cast<const float *>(ws + L.off_scales1),
+                    reinterpret_cast<const float *>(ws + L.off_zeros1), (int64_t)(L.meta / sizeof(float)),
+                    n_src, tokens, hidden, group, bits_rs, bits_ag, ws + L.off_codes2,
+                    reinterpret_cast<float *>(ws + L.off_scales2), reinterpret_cast<float *>(ws + L.off_zeros2),
+                    hip_stream);
+    if (rc != FC_OK) return rc;
+    return dequantize_rot_impl(quantizer, ws + L.off_codes2, reinterpret_cast<const float *>(ws + L.off_scales2),
+                               reinterpret_cast<const float *>(ws + L.off_zeros2), tokens, hidden, group,
+                               bits_ag, y_f16, hip_stream);
 }
 
 const char *fc_strerror(int code)

@@ -51,6 +51,12 @@ hipError_t launch_quantize_wide(int bits, int codec, const void *x_f16, int64_t 
                                 void *codes, float *scales, float *zeros, hipStream_t stream);
 hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipStream_t stream);
 
+// Hadamard rotation fused into the quantizer / dequantizer (fc_rot.hip): hidden in {2048, 4096, 8192}.
+hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t tokens, int hidden, int group,
+                               void *codes, float *scales, float *zeros, hipStream_t stream);
+hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,
+                                 int64_t tokens, int hidden, int group, void *y_f16, hipStream_t stream);
+
 inline int log2_int(int v)
 {
     int s = 0;

@@ -33,6 +33,8 @@ class Workload:
     quantizer: str = "asym"   # "asym": Eq. 1-2 (scale + zero-point), "sym": Eq. 3-4 (scale only),
                               # "fp8": E4M3 bytes with a per-group scale (the paper's FP8_Sym rows)
 
+    rotate: bool = False      # Hadamard rotation around the all-reduce (Section 4 of the paper)
+
     @property
     def elements(self) -> int:
         return self.tokens * self.hidden
@@ -57,6 +59,9 @@ WORKLOADS = {
     "llama3_70b_prefill_per_token": Workload("llama3_70b_prefill_per_token", 4, 8192, 8192, 4, 4, 8192),
     "llama3_70b_prefill_fp8": Workload("llama3_70b_prefill_fp8", 4, 8192, 8192, 8, 8, 128, quantizer="fp8"),
     "llama3_8b_prefill_fp8": Workload("llama3_8b_prefill_fp8", 4, 8192, 4096, 8, 8, 128, quantizer="fp8"),
+    "llama3_70b_prefill_per_token_rot": Workload("llama3_70b_prefill_per_token_rot", 4, 8192, 8192, 4, 4, 8192,
+                                                 rotate=True),
+    "llama3_70b_prefill_rot": Workload("llama3_70b_prefill_rot", 4, 8192, 8192, 4, 4, 128, rotate=True),
     "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
 }
 
