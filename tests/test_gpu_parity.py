@@ -382,3 +382,34 @@ def test_full_size_configs_on_sampled_rows(fc, name):
     # scales positive and finite, zero-points integral
     assert bool((so > 0).all()) and bool(torch.isfinite(so).all())
     assert bool((zo == torch.round(zo)).all())
+
+
+def test_entry_points_capture_into_a_hip_graph_and_replay(fc):
+    # the library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so a
+    # whole all-reduce captures into a HIP graph; every replay, with eager work in between, must
+    # reproduce the eager result
+    w = synth_inputs.WORKLOADS["decode"]
+    x = synth_inputs.make_workload(w)
+    xd = dev(x.view(np.uint16)).view(torch.float16)
+    y = torch.empty((w.tokens, w.hidden), dtype=torch.float16, device="cuda")
+    ws = torch.empty(fc.allreduce_sim_workspace_bytes(w.n_src, w.tokens, w.hidden, w.group, w.bits_in, w.bits_out),
+                     dtype=torch.uint8, device="cuda")
+    want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
+    fc.allreduce_sim(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws)      # eager, loads the kernels
+    torch.cuda.synchronize()
+    assert same_bits(y.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        fc.allreduce_sim(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws)
+    for rep in range(4):
+        y.fill_(7.0); ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert same_bits(got.view(np.uint16), want.view(np.uint16)), "replay %d: %s" % (
+            rep, first_diff(got.view(np.uint16), want.view(np.uint16)))
+        # new input for the next replay: the graph reads the buffers, not captured values
+        x = synth_inputs.make_partials(w.n_src, w.tokens, w.hidden, seed=100 + rep)
+        xd.copy_(dev(x.view(np.uint16)).view(torch.float16))
+        want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
