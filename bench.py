@@ -258,6 +258,25 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # the same access pattern without arithmetic (N code slabs in, one slab out), timed the same way
+    slab = T * H * w.bits_in // 8
+    R = [torch.empty(slab, dtype=torch.uint8, device=dev) for _ in range(B)]
+    src = [C1[k].view(N, slab) for k in range(B)]
+    for _ in range(3):
+        for k in range(B):
+            fc.stream_reference(src[k], R[k])
+    sr0, sr1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    sr_reps = max(1, min(a.steps, 100))
+    torch.cuda.synchronize()
+    sr0.record()
+    for _ in range(sr_reps):
+        for k in range(B):
+            fc.stream_reference(src[k], R[k])
+    sr1.record()
+    torch.cuda.synchronize()
+    sr_s = sr0.elapsed_time(sr1) * 1e-3 / (sr_reps * B)
+    sr_bytes = (N + 1) * slab
+
     # mean milliseconds per volume of each stage
     ms = {k: float(sum(s.elapsed_time(e) for s, e, _ in v) / sum(n for _, _, n in v)) for k, v in ev.items()}
     fused_s = ms["f"] * 1e-3
@@ -310,6 +329,14 @@ def main():
             "us_per_launch": round(ms["f"] * 1e3, 2),
             "launches_timed": a.steps * B,
             "traffic": load_traffic(w.name),
+            "stream_reference": {
+                "what": "fc_stream_reference: %d code slabs in, 1 out, the fused kernel's tiling and staging, "
+                        "no arithmetic, no scales / zero-points" % N,
+                "bytes_per_launch": sr_bytes,
+                "us_per_launch": round(sr_s * 1e6, 2),
+                "GBps": round(sr_bytes / sr_s / 1e9, 1),
+                "fused_over_reference": round(achieved / (sr_bytes / sr_s / 1e9), 4),
+            },
         },
     }
     if not a.no_cpu_baseline:

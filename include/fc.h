@@ -226,6 +226,17 @@ FC_API int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, in
                                 int group, int bits_rs, int bits_ag, int quantizer, void *y_f16,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement aid, not part of the paper's method: the memory access pattern of
+ * fc_dequant_reduce_requant with the arithmetic taken out.  Reads n_src device arrays of `bytes`
+ * bytes (source j at in + j*in_src_stride_bytes) and writes their bytewise XOR to `out` (`bytes`
+ * bytes), with the fused kernel's tiling, staging and cache policy.  bytes % 16 == 0; pointers and
+ * stride 16-byte aligned.  bench.py times it next to the fused kernel to show how much of the
+ * bandwidth this access pattern can reach on the machine at hand.
+ */
+FC_API int fc_stream_reference(const void *in, int64_t in_src_stride_bytes, int n_src, int64_t bytes,
+                               void *out, void *hip_stream);
+
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);
 

@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize_rot.restype = i32
         L.fc_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim_rot.restype = i32
+        L.fc_stream_reference.argtypes = [vp, i64, i32, i64, vp, vp]
+        L.fc_stream_reference.restype = i32
         L.fc_strerror.argtypes = [i32]
         L.fc_strerror.restype = ctypes.c_char_p
         L.fc_last_hip_error.argtypes = []
@@ -425,3 +427,13 @@ def allreduce_sim_rot(x, group: int, bits_rs: int, bits_ag: int, quantizer: int 
                                       y.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
            "fc_allreduce_sim_rot")
     return y
+
+
+def stream_reference(src, out):
+    """fc_stream_reference (measurement aid): src u8 [N, bytes], out u8 [bytes] = XOR over the N rows."""
+    torch = _torch()
+    _dev(src, torch.uint8, "src"); _dev(out, torch.uint8, "out")
+    n, nbytes = src.shape[0], src[0].numel()
+    _check(lib().fc_stream_reference(src.data_ptr(), src.stride(0) if n > 1 else 0, n, nbytes, out.data_ptr(),
+                                     _stream()), "fc_stream_reference")
+    return out

@@ -70,4 +70,31 @@ hipError_t launch_dequantize(int bits, int codec, const void *codes, const float
     return hipGetLastError();
 }
 
+template <int NSRC>
+static void launch_sr(dim3 grid, hipStream_t stream, const uint8_t *in, int64_t in_stride, int64_t bytes, uint8_t *out)
+{
+    k_stream_reference<NSRC><<<grid, dim3(kBlockThreads), 0, stream>>>(in, in_stride, bytes, out);
+}
+
+hipError_t launch_stream_reference(const void *in, int64_t in_stride, int n_src, int64_t bytes, void *out,
+                                   hipStream_t stream)
+{
+    const uint8_t *i = static_cast<const uint8_t *>(in);
+    uint8_t *o = static_cast<uint8_t *>(out);
+    const int64_t tile = kBlockThreads * 16;
+    const dim3 grid((unsigned)((bytes + tile - 1) / tile));
+    switch (n_src) {
+    case 1: launch_sr<1>(grid, stream, i, in_stride, bytes, o); break;
+    case 2: launch_sr<2>(grid, stream, i, in_stride, bytes, o); break;
+    case 3: launch_sr<3>(grid, stream, i, in_stride, bytes, o); break;
+    case 4: launch_sr<4>(grid, stream, i, in_stride, bytes, o); break;
+    case 5: launch_sr<5>(grid, stream, i, in_stride, bytes, o); break;
+    case 6: launch_sr<6>(grid, stream, i, in_stride, bytes, o); break;
+    case 7: launch_sr<7>(grid, stream, i, in_stride, bytes, o); break;
+    case 8: launch_sr<8>(grid, stream, i, in_stride, bytes, o); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace fc

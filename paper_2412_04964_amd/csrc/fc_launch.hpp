@@ -57,6 +57,10 @@ hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t t
 hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,
                                  int64_t tokens, int hidden, int group, void *y_f16, hipStream_t stream);
 
+// measurement aid: n_src streams of `bytes` in, one out, the fused kernel's access pattern without arithmetic
+hipError_t launch_stream_reference(const void *in, int64_t in_stride, int n_src, int64_t bytes, void *out,
+                                   hipStream_t stream);
+
 inline int log2_int(int v)
 {
     int s = 0;

@@ -413,3 +413,14 @@ def test_entry_points_capture_into_a_hip_graph_and_replay(fc):
         x = synth_inputs.make_partials(w.n_src, w.tokens, w.hidden, seed=100 + rep)
         xd.copy_(dev(x.view(np.uint16)).view(torch.float16))
         want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
+
+
+@pytest.mark.parametrize("n_src", [1, 3, 8])
+def test_stream_reference_is_the_xor_of_its_inputs(fc, n_src):
+    rng = np.random.default_rng(n_src)
+    nbytes = 3 * 4096 + 1040                 # several tiles and a ragged tail
+    src = rng.integers(0, 256, size=(n_src, nbytes), dtype=np.uint8)
+    out = Guarded((nbytes,), torch.uint8)
+    fc.stream_reference(dev(src), out.t)
+    torch.cuda.synchronize(); out.check()
+    assert np.array_equal(out.t.cpu().numpy(), np.bitwise_xor.reduce(src, axis=0))
