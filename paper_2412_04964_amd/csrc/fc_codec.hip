@@ -73,7 +73,7 @@ hipError_t launch_dequantize(int bits, int codec, const void *codes, const float
 template <int NSRC>
 static void launch_sr(dim3 grid, hipStream_t stream, const uint8_t *in, int64_t in_stride, int64_t bytes, uint8_t *out)
 {
-    k_stream_reference<NSRC><<<grid, dim3(kBlockThreads), 0, stream>>>(in, in_stride, bytes, out);
+    k_stream_reference<NSRC><<<grid, dim3(fused_block_threads(1)), 0, stream>>>(in, in_stride, bytes, out);
 }
 
 hipError_t launch_stream_reference(const void *in, int64_t in_stride, int n_src, int64_t bytes, void *out,
@@ -81,7 +81,7 @@ hipError_t launch_stream_reference(const void *in, int64_t in_stride, int n_src,
 {
     const uint8_t *i = static_cast<const uint8_t *>(in);
     uint8_t *o = static_cast<uint8_t *>(out);
-    const int64_t tile = kBlockThreads * 16;
+    const int64_t tile = fused_block_threads(1) * 16;
     const dim3 grid((unsigned)((bytes + tile - 1) / tile));
     switch (n_src) {
     case 1: launch_sr<1>(grid, stream, i, in_stride, bytes, o); break;

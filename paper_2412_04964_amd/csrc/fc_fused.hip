@@ -16,12 +16,13 @@ namespace fc {
 template <int NSRC, int LPG>
 static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 {
-    const int64_t tile = block_elems(FC_BITS_IN);
+    constexpr int BT = fused_block_threads(LPG);
+    const int64_t tile = (int64_t)BT * lane_elems(FC_BITS_IN);
     const int64_t blocks = (a.n_elems + tile - 1) / tile;
 #if FC_BITS_IN == 8 && FC_BITS_OUT == 8
     if (a.codec == CODEC_FP8) {
         k_dequant_reduce_requant_sym<8, 8, NSRC, LPG, true>
-            <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
                 a.n_elems, a.group / lane_elems(8), log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
@@ -30,7 +31,7 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 #endif
     if (a.codec == CODEC_SYM) {
         k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
-            <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
                 a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
@@ -38,7 +39,7 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
     }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
-        <<<dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream>>>(
+        <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
             a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
             static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
