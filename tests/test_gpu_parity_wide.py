@@ -152,3 +152,37 @@ def test_ablation_sweep_matches_oracle_errors(fc):
             y = fn(x, r["group"], b_rs, b_ag)
         want = float(np.mean((y.astype(np.float64) - exact) ** 2))
         assert abs(r["mse"] - want) <= 1e-4 * want, r
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_shapes_all_quantizers(fc, seed):
+    # seeded sweep over shapes, group sizes, fan-ins and code widths that no other test names explicitly
+    from test_gpu_parity_fp8 import gpu_fused_fp8, gpu_quantize_fp8, oracle_stage1_fp8
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(14):
+        group = int(rng.choice([32, 64, 128, 256, 512, 1024, 2048, 4096]))
+        hidden = group * int(rng.integers(1, max(2, 12288 // group) + 1))
+        tokens = int(rng.integers(1, 7))
+        n_src = int(rng.integers(1, 9))
+        bits_in, bits_out = int(rng.choice([4, 8])), int(rng.choice([4, 8]))
+        what = "seed %d case %d: N=%d %dx%d g=%d %d->%d" % (seed, case, n_src, tokens, hidden, group, bits_in, bits_out)
+        x = synth_inputs.make_partials(n_src, tokens, hidden, seed=seed * 100 + case,
+                                       outlier_frac=float(rng.choice([0.0, 0.01, 0.1])))
+        c, s, z = oracle_stage1(x, group, bits_in)
+        assert_triplet(gpu_quantize(fc, x[0], group, bits_in), (c[0], s[0], z[0]), what + " quantize")
+        want = oracle.dequant_reduce_requant(c, s, z, hidden, group, bits_in, bits_out)
+        assert_triplet(gpu_fused(fc, c, s, z, hidden, group, bits_in, bits_out), want, what + " fused")
+        wy = oracle.dequantize(*want, hidden, group, bits_out)
+        gy = gpu_dequantize(fc, *want, hidden, group, bits_out)
+        assert same_bits(gy.view(np.uint16), wy.view(np.uint16)), what + " dequantize"
+        c, s = oracle_stage1_sym(x, group, bits_in)
+        assert_pair(gpu_quantize_sym(fc, x[0], group, bits_in), (c[0], s[0]), what + " quantize_sym")
+        want = oracle.dequant_reduce_requant_sym(c, s, hidden, group, bits_in, bits_out)
+        assert_pair(gpu_fused_sym(fc, c, s, hidden, group, bits_in, bits_out), want, what + " fused_sym")
+        wy = oracle.dequantize_sym(*want, hidden, group, bits_out)
+        gy = gpu_dequantize_sym(fc, *want, hidden, group, bits_out)
+        assert same_bits(gy.view(np.uint16), wy.view(np.uint16)), what + " dequantize_sym"
+        c, s = oracle_stage1_fp8(x, group)
+        assert_pair(gpu_quantize_fp8(fc, x[0], group), (c[0], s[0]), what + " quantize_fp8")
+        want = oracle.dequant_reduce_requant_fp8(c, s, hidden, group)
+        assert_pair(gpu_fused_fp8(fc, c, s, hidden, group), want, what + " fused_fp8")
