@@ -186,3 +186,40 @@ def test_random_shapes_all_quantizers(fc, seed):
         assert_pair(gpu_quantize_fp8(fc, x[0], group), (c[0], s[0]), what + " quantize_fp8")
         want = oracle.dequant_reduce_requant_fp8(c, s, hidden, group)
         assert_pair(gpu_fused_fp8(fc, c, s, hidden, group), want, what + " fused_fp8")
+
+
+def test_large_volume_offsets_beyond_32_bits(fc):
+    # 2^33 elements: byte offsets of the input exceed 2^34 and element indices 2^32, with a ragged last tile;
+    # sampled rows (first, last, around the 2^32-element and 2^32-byte marks) are checked against the oracle
+    hidden, group, bits = 8192, 128, 4
+    tokens = (1 << 20) + 3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80 * (1 << 30):
+        pytest.skip("needs 80 GB of free device memory")
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    x = torch.empty((tokens, hidden), dtype=torch.float16, device="cuda")
+    chunk = 1 << 16
+    for r0 in range(0, tokens, chunk):
+        r1 = min(tokens, r0 + chunk)
+        x[r0:r1] = (torch.randn((r1 - r0, hidden), generator=g, device="cuda") * (1.0 + (r0 // chunk) % 5)).half()
+    c = torch.empty((2, tokens, hidden // 2), dtype=torch.uint8, device="cuda")
+    s = torch.empty((2, tokens, hidden // group), dtype=torch.float32, device="cuda")
+    z = torch.empty_like(s)
+    fc.quantize(x, group, bits, out=(c[0], s[0], z[0]))
+    x2 = x.flip(1)                                        # second partial: the same values mirrored along hidden
+    fc.quantize(x2, group, bits, out=(c[1], s[1], z[1]))
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, hidden, group, bits, bits)
+    y = fc.dequantize(co, so, zo, hidden, group, bits)
+    torch.cuda.synchronize()
+    marks = [0, 1, (1 << 32) // hidden - 1, (1 << 32) // hidden, (1 << 31) // hidden, (1 << 33) // (2 * hidden) - 1,
+             (1 << 19) + 1, tokens - 4, tokens - 3, tokens - 2, tokens - 1]
+    rows = np.unique(np.array(marks + list(np.random.default_rng(6).integers(0, tokens, 20))))
+    ridx = torch.from_numpy(rows).cuda()
+    xs = np.stack([x[ridx].cpu().numpy(), x2[ridx].cpu().numpy()])
+    oc, os_, oz = oracle_stage1(xs, group, bits)
+    assert_triplet((c[:, ridx].cpu().numpy(), s[:, ridx].cpu().numpy(), z[:, ridx].cpu().numpy()), (oc, os_, oz),
+                   "large volume stage 1")
+    want = oracle.dequant_reduce_requant(oc, os_, oz, hidden, group, bits, bits)
+    assert_triplet((co[ridx].cpu().numpy(), so[ridx].cpu().numpy(), zo[ridx].cpu().numpy()), want, "large volume fused")
+    wy = oracle.dequantize(*want, hidden, group, bits)
+    assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), "large volume output"
