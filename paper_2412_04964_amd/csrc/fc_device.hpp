@@ -1,13 +1,17 @@
 // fc_device.hpp -- gfx950 device code of the Flash Communication quantization
-// path: the group quantizer (paper Appendix, Eq. 1-2), its inverse, and the fused
-// Dequantize x N -> ReduceSum -> FinegrainedQuantize body of Algorithm 1.
+// path: the group quantizers (paper Appendix, Eq. 1-2 asymmetric, Eq. 3-4
+// symmetric, and the FP8 E4M3 variant of the paper's precision table), their
+// inverses, and the fused Dequantize x N -> ReduceSum -> FinegrainedQuantize body
+// of Algorithm 1.  Groups wider than this file's kernels handle and the Hadamard
+// rotation are in fc_wide.hip and fc_rot.hip, built from the same functions.
 //
 // Work decomposition (wave64).  On the code side every lane owns exactly one
 // 128-bit access: EPL = 32 consecutive elements for 4-bit codes, 16 for 8-bit
 // codes.  A group of g elements is therefore LPG = g/EPL adjacent lanes (4 lanes
 // = one DPP quad for g = 128 at 4 bit), a wavefront covers 64*EPL elements and a
-// 256-thread workgroup four times that.  The per-group min/max is reduced in the
-// lane first and then across the LPG lanes with DPP row operations.
+// workgroup of 2 or 4 wavefronts that many times more.  The per-group min/max is
+// reduced in the lane first, then across the LPG lanes with DPP row operations
+// (and, for groups of 128 or 256 lanes, across wavefronts through LDS).
 //
 // Memory access.  Every global access instruction of the bulk streams is one
 // fully coalesced 128-bit-per-lane access (lane l of a wavefront touches bytes
@@ -31,17 +35,10 @@
 
 namespace fc {
 
-#ifndef FC_BLOCK_THREADS
-#define FC_BLOCK_THREADS 256                         // 4 wavefronts
-#endif
-constexpr int kBlockThreads = FC_BLOCK_THREADS;
+constexpr int kBlockThreads = 256;                   // 4 wavefronts
 constexpr int kBlockWaves = kBlockThreads / 64;
 
-#ifdef FC_WAVES_PER_EU
-#define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(FC_WAVES_PER_EU)))
-#else
 #define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads)
-#endif
 
 // quantizer selected by a template argument of the kernels
 constexpr int kAsym = 0;    // Eq. 1-2: unsigned codes, scale and zero-point
@@ -783,8 +780,9 @@ __device__ __forceinline__ void accumulate_general(const u32 (&w)[4], float s, f
 }
 
 // ---------------------------------------------------------------------------
-// Kernels.  One workgroup = 256 threads = 4 wavefronts; wavefronts never
-// synchronize with each other (every LDS region is private to one wavefront).
+// Kernels.  One workgroup = 2 or 4 wavefronts; wavefronts never synchronize
+// with each other (every LDS region is private to one wavefront) except for the
+// one barrier of a group that spans several wavefronts.
 // ---------------------------------------------------------------------------
 
 // FinegrainedQuantize of binary16 input (Algorithm 1, first quantization).
@@ -848,7 +846,7 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
 // Dequantize x NSRC, ReduceSum, FinegrainedQuantize (Algorithm 1, loop body
 // between the two exchanges).  The fp32 sum lives in registers only.
 //
-// One tile of 256*EPL elements per workgroup, one wavefront tile per wavefront.
+// One tile of BT*EPL elements per workgroup (BT = fused_block_threads(LPG)), one wavefront tile per wavefront.
 // Fan-in staging: at wavefront start every lane issues, for each of the NSRC
 // sources, one 128-bit buffer load that the memory pipeline writes straight into
 // the wavefront's LDS landing zone (1 KB per source), bypassing the vector
