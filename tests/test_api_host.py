@@ -114,3 +114,48 @@ def test_binding_refuses_cpu_tensors():
     import paper_2412_04964_amd as fc
     with pytest.raises(TypeError):
         fc.quantize(torch.zeros(4, 256, dtype=torch.float16), 128, 8)
+
+
+def test_variant_entry_points_argument_checks(L):
+    # symmetric and FP8: the same checks minus the zero-point arrays
+    assert L.fc_quantize_sym(P, 4, 256, 128, 5, P, P, None) == -2
+    assert L.fc_quantize_sym(P, 4, 256, 128, 4, P, None, None) == -1
+    assert L.fc_quantize_sym(P, 4, 256, 128, 4, P + 8, P, None) == -5
+    assert L.fc_quantize_sym(None, 0, 256, 128, 4, None, None, None) == 0
+    assert L.fc_quantize_fp8(P, 4, 256, 100, P, P, None) == -3
+    assert L.fc_quantize_fp8(None, 4, 256, 128, P, P, None) == -1
+    cs = 4 * 256
+    assert L.fc_dequant_reduce_requant_fp8(P, cs - 16, P, 8, 4, 4, 256, 128, P, P, None) == -4
+    assert L.fc_dequant_reduce_requant_fp8(P, cs, P, 1, 4, 4, 256, 128, P, P, None) == -4
+    assert L.fc_dequant_reduce_requant_sym(P, cs // 2, P, 8, 9, 4, 256, 128, 4, 4, P, P, None) == -4
+    assert L.fc_dequant_reduce_requant_sym(P, cs // 2, P, 8, 4, 4, 256, 128, 4, 4, P, None, None) == -1
+    assert L.fc_dequantize_sym(P, P, 4, 256, 128, 4, None, None) == -1
+    assert L.fc_dequantize_fp8(P, P + 4, 4, 256, 128, P, None) == -5
+    need = L.fc_allreduce_sim_workspace_bytes(4, 16, 4096, 128, 8, 8)
+    assert L.fc_allreduce_sim_fp8(P, 4, 16, 4096, 128, P, P, need - 1, None) == -6
+    assert L.fc_allreduce_sim_sym(P, 4, 16, 4096, 128, 4, 4, P, None, need, None) == -6
+
+
+def test_rotation_and_stream_reference_argument_checks(L):
+    q = L.fc_quantize_rot
+    assert q(P, 4, 1024, 128, 4, 0, P, P, P, None) == -4          # hidden must be 2048, 4096 or 8192
+    assert q(P, 4, 6144, 128, 4, 0, P, P, P, None) == -4
+    assert q(P, 4, 4096, 128, 4, 3, P, P, P, None) == -4          # unknown quantizer
+    assert q(P, 4, 4096, 128, 4, 2, P, P, P, None) == -2          # FP8 needs 8 bits
+    assert q(P, 4, 4096, 128, 4, 0, P, P, None, None) == -1       # asymmetric needs zero-points
+    assert q(P, 4, 4096, 8192, 4, 0, P, P, P, None) == -3         # group > hidden
+    assert q(None, 0, 4096, 128, 4, 1, None, None, None, None) == 0
+    d = L.fc_dequantize_rot
+    assert d(P, P, None, 4, 4096, 128, 8, 0, P, None) == -1
+    assert d(P, P, P, 4, 4096, 128, 8, 1, P + 2, None) == -5
+    need = L.fc_allreduce_sim_workspace_bytes(4, 16, 4096, 128, 4, 8)
+    s = L.fc_allreduce_sim_rot
+    assert s(P, 4, 16, 4096, 128, 4, 8, 0, P, P, need - 1, None) == -6
+    assert s(P, 4, 16, 4096, 128, 4, 8, 2, P, P, need, None) == -2
+    assert s(P, 4, 16, 2560, 128, 4, 8, 0, P, P, need, None) == -4
+    r = L.fc_stream_reference
+    assert r(P, 4096, 4, 4096 + 8, P, None) == -4                 # bytes % 16
+    assert r(P, 2048, 4, 4096, P, None) == -4                     # sources would overlap
+    assert r(P, 4096, 0, 4096, P, None) == -4
+    assert r(None, 4096, 4, 4096, P, None) == -1
+    assert r(P, 4096, 4, 0, None, None) == 0
