@@ -874,7 +874,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     struct MetaRec { float s; u32 z; };                       // z: packed halves (fast) or fp32 bits
 
     __shared__ __attribute__((aligned(16))) uint8_t landing[kWaves][NSRC][1024];
-    __shared__ MetaRec meta[kWaves][NSRC * kMaxGw];
+    __shared__ MetaRec meta[(LPG == 0 || LPG >= 8) ? 1 : kWaves][NSRC * kMaxGw];
     __shared__ float slot[LPG == 0 ? kWaves : 1][2];     // cross-wavefront min / max (wide groups)
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
@@ -890,48 +890,87 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
 
-    // --- table loads (small, first: vector-memory results return in issue order).
-    // entry idx = j * gw + g  <->  (source j, group g of the wavefront tile)
-    const int64_t g_wave = (e_tile + (int64_t)wave * kWaveElems) >> group_shift;
-    float ms[K], mz[K];
+    // Scales and zero-points of the sources.  Narrow groups (up to 4 lanes): the NSRC x (64/LPG)
+    // pairs of the wavefront tile are loaded one per lane, checked and converted once, and handed to
+    // the consuming lanes through an LDS table.  Wider groups: every lane loads the pairs of its own
+    // group (few distinct addresses per wavefront); measured, the table costs the 4-bit kernel up to
+    // 14 % once a group spans 8 lanes or more, while the per-lane conversions cost the narrow-group
+    // kernels 1.5 %.
+    constexpr bool kDirectMeta = (LPG == 0 || LPG >= 8);
+    bool all_fast;
+    MetaRec mrec[kDirectMeta ? NSRC : 1];
+    const MetaRec *my_meta = nullptr;
+    if constexpr (kDirectMeta) {
+        const u32 gi_lane = (tid * EPL) >> group_shift;
+        int64_t g_lane = g_tile + gi_lane;
+        g_lane = g_lane < n_groups ? g_lane : n_groups - 1;   // ragged tail: stay inside the array
+        float ms_[NSRC], mz_[NSRC];
 #pragma unroll
-    for (int it = 0; it < K; ++it) {
-        int idx = it * 64 + (int)lane;
-        idx = idx < entries ? idx : 0;                        // surplus lanes re-read entry 0
-        const int j = idx >> gw_shift, g = idx & (gw - 1);
-        int64_t gi = g_wave + g;
-        gi = gi < n_groups ? gi : n_groups - 1;               // ragged tail: stay inside the array
-        const int64_t at = (int64_t)j * meta_stride + gi;
-        ms[it] = scales_in[at];
-        mz[it] = zeros_in[at];
-    }
-    issue_order_fence();
-
-    // --- codes: straight into the landing zone
-#pragma unroll
-    for (int j = 0; j < NSRC; ++j) {
-        const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
-                                    (n_elems - e_tile) * BITS_IN / 8);
-        dma_piece(rc, tid * 16, &landing[wave][j][0]);
-    }
-    issue_order_fence();
-
-    // --- table: check, convert, publish
-    bool ok = true;
-#pragma unroll
-    for (int it = 0; it < K; ++it) ok = ok && zero_is_fast(mz[it]);
-    const bool all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
-#pragma unroll
-    for (int it = 0; it < K; ++it) {
-        const int idx = it * 64 + (int)lane;
-        if (idx < entries) {
-            MetaRec r;
-            r.s = ms[it];
-            r.z = all_fast ? pack_zero_const(mz[it]) : __builtin_bit_cast(u32, mz[it]);
-            meta[wave][idx] = r;
+        for (int j = 0; j < NSRC; ++j) {
+            ms_[j] = scales_in[(int64_t)j * meta_stride + g_lane];
+            mz_[j] = zeros_in[(int64_t)j * meta_stride + g_lane];
         }
+        issue_order_fence();
+#pragma unroll
+        for (int j = 0; j < NSRC; ++j) {
+            const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
+                                        (n_elems - e_tile) * BITS_IN / 8);
+            dma_piece(rc, tid * 16, &landing[wave][j][0]);
+        }
+        issue_order_fence();
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < NSRC; ++j) ok = ok && zero_is_fast(mz_[j]);
+        all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
+#pragma unroll
+        for (int j = 0; j < NSRC; ++j) {
+            mrec[j].s = ms_[j];
+            mrec[j].z = all_fast ? pack_zero_const(mz_[j]) : __builtin_bit_cast(u32, mz_[j]);
+        }
+    } else {
+        // --- table loads (small, first: vector-memory results return in issue order).
+        // entry idx = j * gw + g  <->  (source j, group g of the wavefront tile)
+        const int64_t g_wave = (e_tile + (int64_t)wave * kWaveElems) >> group_shift;
+        float ms[K], mz[K];
+#pragma unroll
+        for (int it = 0; it < K; ++it) {
+            int idx = it * 64 + (int)lane;
+            idx = idx < entries ? idx : 0;                        // surplus lanes re-read entry 0
+            const int j = idx >> gw_shift, g = idx & (gw - 1);
+            int64_t gi = g_wave + g;
+            gi = gi < n_groups ? gi : n_groups - 1;               // ragged tail: stay inside the array
+            const int64_t at = (int64_t)j * meta_stride + gi;
+            ms[it] = scales_in[at];
+            mz[it] = zeros_in[at];
+        }
+        issue_order_fence();
+
+        // --- codes: straight into the landing zone
+#pragma unroll
+        for (int j = 0; j < NSRC; ++j) {
+            const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
+                                        (n_elems - e_tile) * BITS_IN / 8);
+            dma_piece(rc, tid * 16, &landing[wave][j][0]);
+        }
+        issue_order_fence();
+
+        // --- table: check, convert, publish
+        bool ok = true;
+#pragma unroll
+        for (int it = 0; it < K; ++it) ok = ok && zero_is_fast(mz[it]);
+        all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
+#pragma unroll
+        for (int it = 0; it < K; ++it) {
+            const int idx = it * 64 + (int)lane;
+            if (idx < entries) {
+                MetaRec r;
+                r.s = ms[it];
+                r.z = all_fast ? pack_zero_const(mz[it]) : __builtin_bit_cast(u32, mz[it]);
+                meta[wave][idx] = r;
+            }
+        }
+        my_meta = &meta[wave][lane / (u32)lpg_v];
     }
-    const MetaRec *my_meta = &meta[wave][lane / (u32)lpg_v];  // entry 0 when the group spans the wavefront
 
     float acc[EPL];
 #pragma unroll
@@ -945,7 +984,11 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
             // sources (issued after it) are outstanding
             wait_vmem_outstanding(NSRC - 1 - j);
             u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
-            const MetaRec r = my_meta[j * gw];
+            MetaRec r;
+            if constexpr (kDirectMeta)
+                r = mrec[j];
+            else
+                r = my_meta[j * gw];
             lds_read_complete(a);
             const u32 w[4] = {a[0], a[1], a[2], a[3]};
             if constexpr (decltype(fast_tag)::value)
