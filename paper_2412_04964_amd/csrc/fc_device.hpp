@@ -854,9 +854,8 @@ __global__ FC_KERNEL_ATTRS void k_quantize(
 // registers hold only the accumulators and the source being folded in, which
 // keeps 8 wavefronts resident per SIMD.  Each source is read back with one
 // ds_read_b128 per lane (conflict-free) as soon as its load has retired.
-// The group scales / zero-points of the wavefront tile (NSRC x 64/LPG entries)
-// are spread over the lanes, checked and converted once, and passed to the
-// consuming lanes through a small LDS table.
+// The group scales / zero-points reach the lanes in one of two ways, chosen at
+// compile time by the group width (see kDirectMeta below).
 template <int BITS_IN, int BITS_OUT, int NSRC, int LPG>
 __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_requant(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
