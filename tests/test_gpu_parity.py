@@ -424,3 +424,26 @@ def test_stream_reference_is_the_xor_of_its_inputs(fc, n_src):
     fc.stream_reference(dev(src), out.t)
     torch.cuda.synchronize(); out.check()
     assert np.array_equal(out.t.cpu().numpy(), np.bitwise_xor.reduce(src, axis=0))
+
+
+def test_rank_shares_compose_to_the_whole(fc):
+    # sharding by token rows (rank r reduces rows [r T/N, (r+1) T/N) of every source): running the fused
+    # kernel once per share, with offset pointers and the full-slab strides, reproduces the single launch
+    n_src, t, h, group, bits = 4, 24, 4096, 128, 4
+    x = synth_inputs.make_partials(n_src, t, h, seed=21)
+    c, s, z = oracle_stage1(x, group, bits)
+    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits, bits)
+    cd, sd, zd = dev(c), dev(s), dev(z)
+    co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
+    so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
+    zo = torch.empty_like(so)
+    share = t // n_src
+    st = torch.cuda.current_stream().cuda_stream
+    for r in range(n_src):
+        r0 = r * share
+        rc = fc.lib().fc_dequant_reduce_requant(
+            cd[0, r0].data_ptr(), cd.stride(0), sd[0, r0].data_ptr(), zd[0, r0].data_ptr(), sd.stride(0),
+            n_src, share, h, group, bits, bits, co[r0].data_ptr(), so[r0].data_ptr(), zo[r0].data_ptr(), st)
+        assert rc == 0
+    torch.cuda.synchronize()
+    assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "row shares")
