@@ -112,8 +112,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # the part takes a few hundred launches after an idle period to settle its clocks, hence the long warm-up
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="llama3_70b_prefill", choices=sorted(synth_inputs.WORKLOADS))
     ap.add_argument("--batch", type=int, default=0,
                     help="independent volumes per step (0 = enough for >= 4 GiB of traffic per step)")
