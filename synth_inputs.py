@@ -140,3 +140,28 @@ def adversarial_groups(group: int, seed: int = 0) -> np.ndarray:
     row(rng.uniform(-1e-3, 1e-3, g), rng.uniform(0, 6e-5, g), rng.standard_normal(g) * 1000,
         np.abs(rng.standard_normal(g)) + 30.0, -np.abs(rng.standard_normal(g)) - 500.0)
     return np.stack(rows).astype(np.float16)
+
+
+STRESS_KINDS = 6
+
+
+def make_partials_stress(n_src: int, tokens: int, hidden: int, kind: int, seed: int = 0) -> np.ndarray:
+    """float16 [n_src, tokens, hidden] from one of STRESS_KINDS value distributions chosen to reach the
+    corners of the quantizers: 0 plain N(0,1); 1 per-row scales over 22 octaves; 2 a narrow band on a
+    large offset (huge zero-points); 3 half-integers (rounding ties everywhere); 4 sparse large spikes
+    (mostly-zero groups); 5 micro-noise on a constant (near-degenerate groups, float16 extremes)."""
+    rng = np.random.default_rng(seed)
+    shape = (n_src, tokens, hidden)
+    if kind == 0:
+        x = rng.standard_normal(shape)
+    elif kind == 1:
+        x = rng.standard_normal(shape) * np.exp(rng.uniform(-12, 10, (n_src, tokens, 1)))
+    elif kind == 2:
+        x = rng.uniform(100, 101, shape) * rng.choice([-1, 1])
+    elif kind == 3:
+        x = np.round(rng.standard_normal(shape) * 4) / 2
+    elif kind == 4:
+        x = rng.standard_normal(shape) * (rng.random(shape) < 0.02) * 1000
+    else:
+        x = rng.standard_normal(shape) * 1e-6 + rng.choice([0, 3, -500, 60000])
+    return np.clip(x, -65504, 65504).astype(np.float16)

@@ -223,3 +223,33 @@ def test_large_volume_offsets_beyond_32_bits(fc):
     assert_triplet((co[ridx].cpu().numpy(), so[ridx].cpu().numpy(), zo[ridx].cpu().numpy()), want, "large volume fused")
     wy = oracle.dequantize(*want, hidden, group, bits)
     assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), "large volume output"
+
+
+@pytest.mark.parametrize("kind", range(synth_inputs.STRESS_KINDS))
+def test_value_distributions_end_to_end(fc, kind):
+    # every quantizer and the rotation, end to end, on value distributions that reach the corners
+    # (ties, huge zero-points, near-degenerate groups, mostly-zero groups, 22 octaves of scale)
+    rng = np.random.default_rng(50 + kind)
+    for case in range(10):
+        group = int(rng.choice([32, 128, 512, 2048, 8192]))
+        hidden = group * int(rng.integers(1, max(2, 8192 // group) + 1))
+        tokens, n_src = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        bi, bo = int(rng.choice([4, 8])), int(rng.choice([4, 8]))
+        x = synth_inputs.make_partials_stress(n_src, tokens, hidden, kind, seed=kind * 100 + case)
+        xd = dev(x.view(np.uint16)).view(torch.float16)
+        what = "kind %d case %d: N=%d %dx%d g=%d %d->%d" % (kind, case, n_src, tokens, hidden, group, bi, bo)
+        pairs = [("asym", fc.allreduce_sim(xd, group, bi, bo), oracle.allreduce_sim(x, group, bi, bo)),
+                 ("sym", fc.allreduce_sim_sym(xd, group, bi, bo), oracle.allreduce_sim_sym(x, group, bi, bo)),
+                 ("fp8", fc.allreduce_sim_fp8(xd, group), oracle.allreduce_sim_fp8(x, group))]
+        if hidden in (2048, 4096, 8192):
+            q = int(rng.integers(0, 3))
+            b = (8, 8) if q == 2 else (bi, bo)
+            pairs.append(("rot q=%d" % q, fc.allreduce_sim_rot(xd, group, b[0], b[1], q),
+                          oracle.allreduce_sim_rot(x, group, b[0], b[1], q)))
+        c, s, z = oracle_stage1(x, group, bi)
+        assert_triplet(gpu_fused(fc, c, s, z, hidden, group, bi, bo),
+                       oracle.dequant_reduce_requant(c, s, z, hidden, group, bi, bo), what + " fused")
+        for name, got, want in pairs:
+            got = got.cpu().numpy()
+            assert same_bits(got.view(np.uint16), want.view(np.uint16)), "%s %s: %s" % (
+                what, name, first_diff(got.view(np.uint16), want.view(np.uint16)))
