@@ -154,6 +154,8 @@ def _datasets():
     yield "negative", (-np.abs(rng.standard_normal((8, 1024))) - 100).astype(np.float32)
     yield "tiny", (rng.standard_normal((8, 1024)) * 1e-6).astype(np.float32)
     yield "adversarial", synth_inputs.adversarial_groups(128).astype(np.float32)
+    for kind in range(synth_inputs.STRESS_KINDS):
+        yield "stress %d" % kind, synth_inputs.make_partials_stress(1, 8, 1024, kind, seed=kind)[0].astype(np.float32)
 
 
 @pytest.mark.parametrize("bits", [4, 8])
@@ -181,7 +183,9 @@ def test_quantizer_invariants(bits, group):
         err = np.abs(xh.astype(np.float64) - xg.astype(np.float64))
         slop = 1.0 + 2.0 ** -20 * (np.abs(z) + qmax + 4)
         assert np.all(err[~const] <= (0.5 * s.astype(np.float64) * slop)[~const][..., None] + 1e-45), name
-        assert np.array_equal(bits_of(xh[const]), bits_of(xg[const])), name
+        assert np.array_equal(xh[const], xg[const]), name          # by value: a group of mixed +-0 gives +0
+        nz = const & (xg[..., 0] != 0)
+        assert np.array_equal(bits_of(xh[nz]), bits_of(xg[nz])), name
         # monotone: a larger value never gets a smaller code
         order = np.argsort(xg, axis=-1, kind="stable")
         qs = np.take_along_axis(q, order, -1).astype(np.int32)
