@@ -159,3 +159,21 @@ def test_rotation_and_stream_reference_argument_checks(L):
     assert r(P, 4096, 0, 4096, P, None) == -4
     assert r(None, 4096, 4, 4096, P, None) == -1
     assert r(P, 4096, 4, 0, None, None) == 0
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path, L):
+    # include/fc.h must be usable from C99 and C++ and every declaration must resolve in libfc.so
+    import subprocess
+    import paper_2412_04964_amd as fc
+    calls = "\n".join("    p[%d] = (void *)%s;" % (i, n) for i, n in enumerate(declared_functions()))
+    src = tmp_path / "use_fc.c"
+    src.write_text('#include "fc.h"\n#include <stdio.h>\nint main(void) {\n    void *p[64];\n%s\n'
+                   '    printf("%%d %%s\\n", fc_version(), fc_strerror(FC_ERR_GROUP));\n    return p[0] == 0;\n}\n' % calls)
+    inc = os.path.join(ROOT, "include")
+    exe = tmp_path / "use_fc"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-Wno-pedantic", "-I", inc, str(src),
+                        fc.lib_path(), "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
