@@ -5,10 +5,12 @@
 namespace fc {
 
 template <int BITS, int LPG>
-static void launch_q(int codec, dim3 grid, hipStream_t stream, const uint16_t *x, int64_t n_elems, int lpg,
+static void launch_q(int codec, hipStream_t stream, const uint16_t *x, int64_t n_elems, int lpg,
                      int group_shift, uint8_t *c, float *scales, float *zeros)
 {
-    const dim3 block(kBlockThreads);
+    constexpr int BT = quantize_block_threads(BITS, LPG);
+    const int64_t tile = (int64_t)BT * lane_elems(BITS);
+    const dim3 grid((unsigned)((n_elems + tile - 1) / tile)), block(BT);
     if (codec == CODEC_ASYM)
         k_quantize<BITS, LPG, kAsym><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, zeros);
     else if (codec == CODEC_SYM)
@@ -21,15 +23,13 @@ template <int BITS>
 static void launch_q_bits(int codec, hipStream_t stream, const uint16_t *x, int64_t n_elems, int group,
                           uint8_t *c, float *scales, float *zeros)
 {
-    const int64_t tile = block_elems(BITS);
-    const dim3 grid((unsigned)((n_elems + tile - 1) / tile));
     const int lpg = group / lane_elems(BITS), sh = log2_int(group);
     switch (lpg) {
-    case 1: launch_q<BITS, 1>(codec, grid, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
-    case 2: launch_q<BITS, 2>(codec, grid, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
-    case 4: launch_q<BITS, 4>(codec, grid, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
-    case 8: launch_q<BITS, 8>(codec, grid, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
-    default: launch_q<BITS, 0>(codec, grid, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
+    case 1: launch_q<BITS, 1>(codec, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
+    case 2: launch_q<BITS, 2>(codec, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
+    case 4: launch_q<BITS, 4>(codec, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
+    case 8: launch_q<BITS, 8>(codec, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
+    default: launch_q<BITS, 0>(codec, stream, x, n_elems, lpg, sh, c, scales, zeros); break;
     }
 }
 
