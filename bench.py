@@ -13,7 +13,7 @@ launches of one kernel are back to back, so an event pair around a stage
 measures sustained launch-to-launch time.  `--dependent` runs the stages of one
 volume back to back instead (cache-warm hand-over, reported for comparison).
 
-Prints ONE JSON line.  `value` is the metric named in the benchmark spec: achieved
+Prints ONE JSON line.  `value` is the headline metric of this build: achieved
 GB/s of the fused dequant-reduce-requant kernel (algorithmic bytes per launch /
 mean launch duration, HIP events on the launch stream inside the timed region).
 """
