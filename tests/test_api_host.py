@@ -177,3 +177,14 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path, L):
     r = subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_missing_library_fails_loudly():
+    # no CPU fallback: without libfc.so every compute entry of the binding raises at load time
+    import subprocess
+    import sys
+    code = ("import paper_2412_04964_amd as fc\n"
+            "try:\n    fc.lib()\nexcept ImportError as e:\n    print('ImportError:', e)\n    raise SystemExit(3)\n")
+    env = dict(os.environ, FC_LIBRARY="/nonexistent/libfc.so", PYTHONPATH=ROOT)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, cwd=ROOT)
+    assert r.returncode == 3 and "no CPU fallback" in r.stdout, (r.returncode, r.stdout, r.stderr)
