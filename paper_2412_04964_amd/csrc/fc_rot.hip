@@ -172,11 +172,13 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
     }
 
     hadamard_row<BITS, LOGH>(v, row, tid);
-    constexpr float fwd = 1.0f / (float)(1 << ((LOGH + 1) / 2));      // 2^-ceil(n/2)
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) v[p][i] *= fwd;
+    // Forward scaling fwd = 2^-ceil(n/2).  It is a power of two and nothing here is near the ends of
+    // the fp32 range (the transformed values are multiples of 2^-24 below 2^30), so scaling commutes
+    // with every rounding: instead of scaling all values, the group's min and max are scaled (which
+    // gives the scale, reciprocal and zero-point of the scaled values exactly) and the codes are formed
+    // from the unscaled values with the reciprocal times fwd, the same real product and hence the
+    // same rounded one.
+    constexpr float fwd = 1.0f / (float)(1 << ((LOGH + 1) / 2));
 
     // group min / max: inside the wavefront, then across the wavefronts of the sub-tile, then
     // (one group per row of two sub-tiles) across the sub-tiles
@@ -197,15 +199,16 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
     for (int p = 0; p < P; ++p) {
         float s, inv, zf = 0.0f;
         u32 word[4];
+        const float mn_s = mn[p] * fwd, mx_s = mx[p] * fwd;
         if constexpr (CODEC == kFp8) {
-            group_params_absmax<448>(fmaxf(fabsf(mn[p]), fabsf(mx[p])), s, inv);
-            pack_lane_fp8<EPL>(v[p], inv, word);
+            group_params_absmax<448>(fmaxf(fabsf(mn_s), fabsf(mx_s)), s, inv);
+            pack_lane_fp8<EPL>(v[p], inv * fwd, word);
         } else if constexpr (CODEC == kSym) {
-            group_params_sym<BITS>(fmaxf(fabsf(mn[p]), fabsf(mx[p])), s, inv);
-            pack_lane_sym<BITS, EPL>(v[p], inv, word);
+            group_params_sym<BITS>(fmaxf(fabsf(mn_s), fabsf(mx_s)), s, inv);
+            pack_lane_sym<BITS, EPL>(v[p], inv * fwd, word);
         } else {
-            group_params<BITS>(mn[p], mx[p], s, inv, zf);
-            pack_lane<BITS, EPL>(v[p], inv, zf, mx[p], word);
+            group_params<BITS>(mn_s, mx_s, s, inv, zf);
+            pack_lane<BITS, EPL>(v[p], inv * fwd, zf, mx[p], word);
         }
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, rc,
                                                (p * T + tid) * 16, 0, kStreamPolicy);
