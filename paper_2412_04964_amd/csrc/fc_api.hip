@@ -168,9 +168,14 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
 
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
-    for (int j = 0; j < n_src; ++j) {
-        const int q = quantize_impl(codec, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
-                                    ws + L.off_codes1 + (size_t)j * L.codes_rs,
+    // the N partials are N*tokens rows of one tensor; when the workspace slabs need no padding they
+    // are quantized by one launch (what matters for launch-bound volumes), otherwise one by one
+    const bool packed = L.codes_rs == (size_t)n * bits_rs / 8 && L.meta == (size_t)(n / group) * sizeof(float) &&
+                        tokens <= kMaxElems / hidden / n_src;
+    const int launches = packed ? 1 : n_src;
+    for (int j = 0; j < launches; ++j) {
+        const int q = quantize_impl(codec, x + (size_t)j * (size_t)n * 2, packed ? tokens * n_src : tokens, hidden,
+                                    group, bits_rs, ws + L.off_codes1 + (size_t)j * L.codes_rs,
                                     reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
                                     reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta),
                                     hip_stream);
@@ -373,8 +378,12 @@ int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, int64_t h
 
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
-    for (int j = 0; j < n_src; ++j) {
-        rc = quantize_rot_impl(quantizer, x + (size_t)j * (size_t)n * 2, tokens, hidden, group, bits_rs,
+    const bool packed = L.codes_rs == (size_t)n * bits_rs / 8 && L.meta == (size_t)(n / group) * sizeof(float) &&
+                        tokens * n_src <= 0x7FFFFFFF;
+    const int launches = packed ? 1 : n_src;
+    for (int j = 0; j < launches; ++j) {
+        rc = quantize_rot_impl(quantizer, x + (size_t)j * (size_t)n * 2, packed ? tokens * n_src : tokens, hidden,
+                               group, bits_rs,
                                ws + L.off_codes1 + (size_t)j * L.codes_rs,
                                reinterpret_cast<float *>(ws + L.off_scales1 + (size_t)j * L.meta),
                                reinterpret_cast<float *>(ws + L.off_zeros1 + (size_t)j * L.meta), hip_stream);
