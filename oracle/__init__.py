@@ -9,6 +9,7 @@ Array conventions (Algorithm 1 of the paper; groups run along ``hidden``):
   codes   uint8 ``[tokens, hidden*bits/8]`` (INT4: element 2k low nibble, 2k+1 high)
   scales  float32 ``[tokens, hidden/group]``
   zeros   float32 ``[tokens, hidden/group]`` (integer-valued, not clamped)
+  meta    uint32 ``[tokens, hidden/group]`` (compact variant: binary16 scale | binary16 zero << 16)
 """
 from __future__ import annotations
 
@@ -84,6 +85,20 @@ def lib() -> ctypes.CDLL:
         L.fc_ref_quantize_rot.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
         L.fc_ref_dequantize_rot.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp]
         L.fc_ref_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp]
+        L.fc_ref_quantize_group_cmeta_f32.restype = None
+        L.fc_ref_quantize_group_cmeta_f32.argtypes = [vp, i32, i32, vp, vp]
+        L.fc_ref_quantize_cmeta_f32.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.fc_ref_quantize_cmeta.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.fc_ref_dequantize_cmeta_f32.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+        L.fc_ref_dequantize_cmeta.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+        L.fc_ref_dequant_reduce_cmeta_f32.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, vp]
+        L.fc_ref_dequant_reduce_requant_cmeta.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32,
+                                                          vp, vp]
+        L.fc_ref_allreduce_sim_cmeta.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp]
+        for name in ("fc_ref_quantize_cmeta_f32", "fc_ref_quantize_cmeta", "fc_ref_dequantize_cmeta_f32",
+                     "fc_ref_dequantize_cmeta", "fc_ref_dequant_reduce_cmeta_f32",
+                     "fc_ref_dequant_reduce_requant_cmeta", "fc_ref_allreduce_sim_cmeta"):
+            getattr(L, name).restype = i32
         for name in ("fc_ref_hadamard_f32", "fc_ref_quantize_rot", "fc_ref_dequantize_rot",
                      "fc_ref_allreduce_sim_rot"):
             getattr(L, name).restype = i32
@@ -440,4 +455,102 @@ def allreduce_sim_rot(x_f16, group: int, bits_rs: int, bits_ag: int, quantizer: 
     y = np.zeros((t, h), np.uint16)
     _chk(lib().fc_ref_allreduce_sim_rot(_p(x), n, t, h, group, bits_rs, bits_ag, quantizer, _p(y)),
          "allreduce_sim_rot")
+    return y.view(np.float16)
+
+
+# --------------------------------------------------------------------------- #
+# asymmetric quantizer with binary16 metadata: one uint32 word per group,
+# bits 0-15 the scale, bits 16-31 the zero-point (both binary16)
+# --------------------------------------------------------------------------- #
+
+def meta_unpack(meta):
+    """uint32 words -> (scales, zeros) as the float32 values of the two binary16 halves."""
+    m = np.ascontiguousarray(meta, np.uint32)
+    s = (m & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float32)
+    z = (m >> 16).astype(np.uint16).view(np.float16).astype(np.float32)
+    return s, z
+
+
+def quantize_group_cmeta_f32(x, bits: int):
+    """one group of fp32 values -> (codes uint8[g] unpacked, metadata word)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    q = np.zeros(x.size, np.uint8)
+    m = np.zeros(1, np.uint32)
+    lib().fc_ref_quantize_group_cmeta_f32(_p(x), x.size, bits, _p(q), _p(m))
+    return q, int(m[0])
+
+
+def _alloc_cmeta(tokens: int, hidden: int, group: int, bits: int):
+    return np.zeros((tokens, hidden * bits // 8), np.uint8), np.zeros((tokens, hidden // group), np.uint32)
+
+
+def quantize_cmeta_f32(x, group: int, bits: int):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    t, h = x.shape
+    _chk(0 if (h % group == 0 and bits in (4, 8)) else -1, "quantize_cmeta_f32")
+    c, m = _alloc_cmeta(t, h, group, bits)
+    _chk(lib().fc_ref_quantize_cmeta_f32(_p(x), t, h, group, bits, _p(c), _p(m)), "quantize_cmeta_f32")
+    return c, m
+
+
+def quantize_cmeta(x_f16, group: int, bits: int):
+    x = _as_u16(x_f16)
+    t, h = x.shape
+    _chk(0 if (h % group == 0 and bits in (4, 8)) else -1, "quantize_cmeta")
+    c, m = _alloc_cmeta(t, h, group, bits)
+    _chk(lib().fc_ref_quantize_cmeta(_p(x), t, h, group, bits, _p(c), _p(m)), "quantize_cmeta")
+    return c, m
+
+
+def dequantize_cmeta_f32(codes, meta, hidden: int, group: int, bits: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    meta = np.ascontiguousarray(meta, np.uint32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequantize_cmeta_f32(_p(codes), _p(meta), t, hidden, group, bits, _p(y)),
+         "dequantize_cmeta_f32")
+    return y
+
+
+def dequantize_cmeta(codes, meta, hidden: int, group: int, bits: int):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    meta = np.ascontiguousarray(meta, np.uint32)
+    t = codes.shape[0]
+    y = np.zeros((t, hidden), np.uint16)
+    _chk(lib().fc_ref_dequantize_cmeta(_p(codes), _p(meta), t, hidden, group, bits, _p(y)), "dequantize_cmeta")
+    return y.view(np.float16)
+
+
+def _stacked_cmeta(codes_in, meta_in):
+    c = np.ascontiguousarray(codes_in, np.uint8)
+    m = np.ascontiguousarray(meta_in, np.uint32)
+    if c.ndim != 3 or m.ndim != 3 or m.shape[0] != c.shape[0]:
+        raise ValueError("expected codes [N,T,bytes], meta [N,T,groups]")
+    return c, m
+
+
+def dequant_reduce_cmeta_f32(codes_in, meta_in, hidden: int, group: int, bits_in: int):
+    c, m = _stacked_cmeta(codes_in, meta_in)
+    n, t = c.shape[0], c.shape[1]
+    acc = np.zeros((t, hidden), np.float32)
+    _chk(lib().fc_ref_dequant_reduce_cmeta_f32(_p(c), c[0].nbytes, _p(m), m[0].size, n, t, hidden, group,
+                                               bits_in, _p(acc)), "dequant_reduce_cmeta_f32")
+    return acc
+
+
+def dequant_reduce_requant_cmeta(codes_in, meta_in, hidden: int, group: int, bits_in: int, bits_out: int):
+    c, m = _stacked_cmeta(codes_in, meta_in)
+    n, t = c.shape[0], c.shape[1]
+    co, mo = _alloc_cmeta(t, hidden, group, bits_out)
+    _chk(lib().fc_ref_dequant_reduce_requant_cmeta(_p(c), c[0].nbytes, _p(m), m[0].size, n, t, hidden, group,
+                                                   bits_in, bits_out, _p(co), _p(mo)),
+         "dequant_reduce_requant_cmeta")
+    return co, mo
+
+
+def allreduce_sim_cmeta(x_f16, group: int, bits_rs: int, bits_ag: int):
+    x = _as_u16(x_f16)
+    n, t, h = x.shape
+    y = np.zeros((t, h), np.uint16)
+    _chk(lib().fc_ref_allreduce_sim_cmeta(_p(x), n, t, h, group, bits_rs, bits_ag, _p(y)), "allreduce_sim_cmeta")
     return y.view(np.float16)

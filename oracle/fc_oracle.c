@@ -76,6 +76,23 @@
  *   H4  the rotated values go into the quantizer in fp32 (no rounding to
  *       binary16 in between); the result is binary16(RNE) of the inverse transform
  *       of the dequantized fp32 values.
+ * Compact metadata variant (the paper never says how a group's scale and
+ * zero-point are stored or sent; this is the asymmetric quantizer of Eq. 1-2 with
+ * both kept in binary16, 4 bytes per group instead of 8): the fc_ref_*_cmeta
+ * functions, with R1, R2, R4-R8 unchanged and
+ *   C1  the scale of Eq. 1 (after R5) is rounded to binary16, to nearest even,
+ *       and kept inside the positive finite binary16 numbers: a result of zero
+ *       becomes 2^-24 (the smallest subnormal), an overflow becomes 65504; from
+ *       here on s is that binary16 number, so the reciprocal of R4, the
+ *       zero-point and every code are computed from the scale that is stored;
+ *   C2  the zero-point of Eq. 1, computed from that s, is rounded to binary16 the
+ *       same way and saturates at +-65504; the codes of Eq. 2 use the rounded
+ *       value.  Integers up to 2048 are exact in binary16, so nothing changes
+ *       for a group whose range contains zero (0 <= z <= 2^n - 1 there);
+ *   C3  Dequantize is x^ = (q - z) * s with the two stored binary16 numbers
+ *       widened exactly to fp32; the N-way sum is R6;
+ *   C4  one 32-bit word per group: bits 0-15 the scale, bits 16-31 the
+ *       zero-point.
  * Domain: finite inputs.  NaN / Inf inputs: parity unpinned.
  *
  * Build: cc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
@@ -840,5 +857,188 @@ int fc_ref_allreduce_sim_rot(const uint16_t *x_f16, int n_src, int64_t tokens, i
     if (rc == FC_REF_OK)
         rc = fc_ref_dequantize_rot(c2, s2, z2, tokens, hidden, group, bits_ag, quantizer, y_f16);
     free(c1); free(s1); free(z1); free(c2); free(s2); free(z2);
+    return rc;
+}
+
+/* ======================================================================== */
+/* Asymmetric quantization with binary16 metadata -- readings C1-C4 above.   */
+/* ======================================================================== */
+
+static float meta_scale(uint32_t m) { return fc_ref_half_to_float((uint16_t)(m & 0xFFFFu)); }
+static float meta_zero(uint32_t m) { return fc_ref_half_to_float((uint16_t)(m >> 16)); }
+
+/* Eq. 1-2 on ONE group with the scale and the zero-point held in binary16.
+   q: g codes, one per byte (not packed); *meta: the group's word (C4). */
+void fc_ref_quantize_group_cmeta_f32(const float *x, int g, int bits, uint8_t *q, uint32_t *meta)
+{
+    const float qmax = (float)((1 << bits) - 1);
+    float mn = x[0], mx = x[0];
+    for (int k = 1; k < g; ++k) {
+        if (x[k] < mn) mn = x[k];
+        if (x[k] > mx) mx = x[k];
+    }
+    float s = (mx - mn) / qmax;                  /* Eq. 1, scale */
+    if (!(s >= FLT_MIN)) {                       /* R5 */
+        const float a = fabsf(mn);
+        s = (a >= FLT_MIN) ? a : 1.0f;
+    }
+    uint16_t sh = fc_ref_float_to_half(s);       /* C1 */
+    if (sh == 0x0000u) sh = 0x0001u;             /*   2^-24 */
+    if (sh == 0x7C00u) sh = 0x7BFFu;             /*   65504 */
+    s = fc_ref_half_to_float(sh);
+    const float inv = 1.0f / s;                  /* R4 */
+    float zf = 0.0f - rintf(mn * inv);           /* Eq. 1, zero-point */
+    uint16_t zh = fc_ref_float_to_half(zf);      /* C2 */
+    if ((zh & 0x7FFFu) == 0x7C00u) zh = (uint16_t)((zh & 0x8000u) | 0x7BFFu);
+    zf = fc_ref_half_to_float(zh);
+    for (int k = 0; k < g; ++k) {
+        const float t = rintf(x[k] * inv);       /* Eq. 2 */
+        float u = t + zf;
+        if (u < 0.0f) u = 0.0f;
+        if (u > qmax) u = qmax;
+        q[k] = (uint8_t)u;
+    }
+    *meta = (uint32_t)sh | ((uint32_t)zh << 16);
+}
+
+int fc_ref_quantize_cmeta_f32(const float *x, int64_t tokens, int64_t hidden, int group, int bits,
+                              uint8_t *codes, uint32_t *meta)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x || !codes || !meta) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    uint8_t *q = (uint8_t *)malloc((size_t)hidden);
+    if (!q) return FC_REF_NO_MEM;
+    for (int64_t t = 0; t < tokens; ++t) {
+        for (int64_t c = 0; c < gpr; ++c)
+            fc_ref_quantize_group_cmeta_f32(x + t * hidden + c * group, group, bits, q + c * group,
+                                            &meta[t * gpr + c]);
+        pack_row(q, hidden, bits, codes + t * row_bytes);
+    }
+    free(q);
+    return FC_REF_OK;
+}
+
+int fc_ref_quantize_cmeta(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                          uint8_t *codes, uint32_t *meta)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!x_f16 || !codes || !meta) return FC_REF_BAD_ARG;
+    float *xf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!xf) return FC_REF_NO_MEM;
+    for (int64_t i = 0; i < tokens * hidden; ++i) xf[i] = fc_ref_half_to_float(x_f16[i]);
+    const int rc = fc_ref_quantize_cmeta_f32(xf, tokens, hidden, group, bits, codes, meta);
+    free(xf);
+    return rc;
+}
+
+/* C3, fp32 result */
+int fc_ref_dequantize_cmeta_f32(const uint8_t *codes, const uint32_t *meta,
+                                int64_t tokens, int64_t hidden, int group, int bits, float *y)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !meta || !y) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const uint32_t m = meta[t * gpr + h / group];
+            const float d = (float)code_at(codes + t * row_bytes, h, bits) - meta_zero(m);
+            y[t * hidden + h] = d * meta_scale(m);
+        }
+    return FC_REF_OK;
+}
+
+/* C3, binary16 result (Algorithm 1, last Dequantize) */
+int fc_ref_dequantize_cmeta(const uint8_t *codes, const uint32_t *meta,
+                            int64_t tokens, int64_t hidden, int group, int bits, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes || !meta || !y_f16) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const uint32_t m = meta[t * gpr + h / group];
+            const float d = (float)code_at(codes + t * row_bytes, h, bits) - meta_zero(m);
+            y_f16[t * hidden + h] = fc_ref_float_to_half(d * meta_scale(m));
+        }
+    return FC_REF_OK;
+}
+
+/* Dequantize x N and ReduceSum (R6); source j's words start at meta_in + j*meta_stride. */
+int fc_ref_dequant_reduce_cmeta_f32(const uint8_t *codes_in, int64_t codes_stride,
+                                    const uint32_t *meta_in, int64_t meta_stride,
+                                    int n_src, int64_t tokens, int64_t hidden, int group, int bits_in,
+                                    float *acc)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || n_src < 1) return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    if (!codes_in || !meta_in || !acc) return FC_REF_BAD_ARG;
+    const int64_t gpr = hidden / group;
+    const int64_t row_bytes = hidden * bits_in / 8;
+    for (int64_t t = 0; t < tokens; ++t)
+        for (int64_t h = 0; h < hidden; ++h) {
+            const int64_t gi = t * gpr + h / group;
+            float a = 0.0f;
+            for (int j = 0; j < n_src; ++j) {
+                const uint8_t *row = codes_in + (int64_t)j * codes_stride + t * row_bytes;
+                const uint32_t m = meta_in[(int64_t)j * meta_stride + gi];
+                const float d = (float)code_at(row, h, bits_in) - meta_zero(m);
+                a = fmaf(d, meta_scale(m), a);
+            }
+            acc[t * hidden + h] = a;
+        }
+    return FC_REF_OK;
+}
+
+int fc_ref_dequant_reduce_requant_cmeta(const uint8_t *codes_in, int64_t codes_stride,
+                                        const uint32_t *meta_in, int64_t meta_stride,
+                                        int n_src, int64_t tokens, int64_t hidden, int group,
+                                        int bits_in, int bits_out,
+                                        uint8_t *codes_out, uint32_t *meta_out)
+{
+    if (!check_shape(tokens, hidden, group, bits_in) || !check_shape(tokens, hidden, group, bits_out)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    float *acc = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
+    if (!acc) return FC_REF_NO_MEM;
+    int rc = fc_ref_dequant_reduce_cmeta_f32(codes_in, codes_stride, meta_in, meta_stride, n_src,
+                                             tokens, hidden, group, bits_in, acc);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_quantize_cmeta_f32(acc, tokens, hidden, group, bits_out, codes_out, meta_out);
+    free(acc);
+    return rc;
+}
+
+int fc_ref_allreduce_sim_cmeta(const uint16_t *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                               int group, int bits_rs, int bits_ag, uint16_t *y_f16)
+{
+    if (!check_shape(tokens, hidden, group, bits_rs) || !check_shape(tokens, hidden, group, bits_ag)
+        || n_src < 1)
+        return FC_REF_BAD_ARG;
+    if (tokens == 0) return FC_REF_OK;
+    const int64_t m = tokens * hidden, ng = m / group;
+    const int64_t cb_rs = m * bits_rs / 8, cb_ag = m * bits_ag / 8;
+    uint8_t *c1 = (uint8_t *)malloc((size_t)(cb_rs * n_src));
+    uint32_t *m1 = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(ng * n_src));
+    uint8_t *c2 = (uint8_t *)malloc((size_t)cb_ag);
+    uint32_t *m2 = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)ng);
+    int rc = (c1 && m1 && c2 && m2) ? FC_REF_OK : FC_REF_NO_MEM;
+    for (int j = 0; rc == FC_REF_OK && j < n_src; ++j)
+        rc = fc_ref_quantize_cmeta(x_f16 + (int64_t)j * m, tokens, hidden, group, bits_rs,
+                                   c1 + (int64_t)j * cb_rs, m1 + (int64_t)j * ng);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequant_reduce_requant_cmeta(c1, cb_rs, m1, ng, n_src, tokens, hidden, group,
+                                                 bits_rs, bits_ag, c2, m2);
+    if (rc == FC_REF_OK)
+        rc = fc_ref_dequantize_cmeta(c2, m2, tokens, hidden, group, bits_ag, y_f16);
+    free(c1); free(m1); free(c2); free(m2);
     return rc;
 }
