@@ -37,7 +37,8 @@ HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
 
 def fused_bytes(w) -> int:
     """Algorithmic bytes of one fused launch: N x (codes + meta) in, codes + meta out; meta is an
-    fp32 scale and zero-point per group (8 bytes), or the scale alone (4) for the symmetric quantizer."""
+    fp32 scale and zero-point per group (8 bytes), the scale alone (4) for the symmetric quantizers, or
+    a binary16 scale and zero-point in one word (4) for the compact-metadata variant."""
     m = w.elements
     mb = w.meta_bytes_per_group
     return w.n_src * (m * w.bits_in // 8 + mb * m // w.group) + m * w.bits_out // 8 + mb * m // w.group
@@ -77,14 +78,16 @@ def cpu_baseline(w, x_host, budget_s=20.0):
     if est * 3 > budget_s:
         rows = max(16, int(w.tokens * budget_s / (est * 3)))
     xs = x_host[:, :rows]
-    sym, fp8 = w.quantizer == "sym", w.quantizer == "fp8"
+    sym, fp8, cm = w.quantizer == "sym", w.quantizer == "fp8", w.quantizer == "cmeta"
     if fp8:
         parts = [oracle.quantize_fp8(xs[j], w.group) for j in range(w.n_src)]
+    elif cm:
+        parts = [oracle.quantize_cmeta(xs[j], w.group, w.bits_in) for j in range(w.n_src)]
     else:
         parts = [(oracle.quantize_sym if sym else oracle.quantize)(xs[j], w.group, w.bits_in)
                  for j in range(w.n_src)]
     c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
-    z = None if (sym or fp8) else np.stack([p[2] for p in parts])
+    z = None if (sym or fp8 or cm) else np.stack([p[2] for p in parts])
     best = None
     for _ in range(2):
         t0 = time.perf_counter()
@@ -92,6 +95,8 @@ def cpu_baseline(w, x_host, budget_s=20.0):
             oracle.dequant_reduce_requant_fp8(c, s, w.hidden, w.group)
         elif sym:
             oracle.dequant_reduce_requant_sym(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
+        elif cm:
+            oracle.dequant_reduce_requant_cmeta(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
         else:
             oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
         dt = time.perf_counter() - t0
@@ -157,9 +162,11 @@ def main():
     Z2 = [torch.empty_like(S2[0]) for _ in range(B)]
     Y = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in range(B)]
 
-    sym, fp8 = w.quantizer == "sym", w.quantizer == "fp8"
-
-    qz = {"asym": fc.QUANTIZER_ASYM, "sym": fc.QUANTIZER_SYM, "fp8": fc.QUANTIZER_FP8}[w.quantizer]
+    sym, fp8, cm = w.quantizer == "sym", w.quantizer == "fp8", w.quantizer == "cmeta"
+    qz = {"asym": fc.QUANTIZER_ASYM, "sym": fc.QUANTIZER_SYM, "fp8": fc.QUANTIZER_FP8}.get(w.quantizer)
+    assert not (w.rotate and qz is None), "the rotation entry points take the fp32-metadata quantizers only"
+    M1 = [t.view(torch.int32) for t in S1]          # the compact-metadata words live in the scale buffers
+    M2 = [t.view(torch.int32) for t in S2]
 
     def stage_quantize(k):
         for j in range(N):
@@ -169,6 +176,8 @@ def main():
                 fc.quantize_fp8(X[k][j], g, out=(C1[k][j], S1[k][j]))
             elif sym:
                 fc.quantize_sym(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j]))
+            elif cm:
+                fc.quantize_cmeta(X[k][j], g, w.bits_in, out=(C1[k][j], M1[k][j]))
             else:
                 fc.quantize(X[k][j], g, w.bits_in, out=(C1[k][j], S1[k][j], Z1[k][j]))
 
@@ -177,6 +186,8 @@ def main():
             fc.dequant_reduce_requant_fp8(C1[k], S1[k], H, g, out=(C2[k], S2[k]))
         elif sym:
             fc.dequant_reduce_requant_sym(C1[k], S1[k], H, g, w.bits_in, w.bits_out, out=(C2[k], S2[k]))
+        elif cm:
+            fc.dequant_reduce_requant_cmeta(C1[k], M1[k], H, g, w.bits_in, w.bits_out, out=(C2[k], M2[k]))
         else:
             fc.dequant_reduce_requant(C1[k], S1[k], Z1[k], H, g, w.bits_in, w.bits_out,
                                       out=(C2[k], S2[k], Z2[k]))
@@ -188,6 +199,8 @@ def main():
             fc.dequantize_fp8(C2[k], S2[k], H, g, out=Y[k])
         elif sym:
             fc.dequantize_sym(C2[k], S2[k], H, g, w.bits_out, out=Y[k])
+        elif cm:
+            fc.dequantize_cmeta(C2[k], M2[k], H, g, w.bits_out, out=Y[k])
         else:
             fc.dequantize(C2[k], S2[k], Z2[k], H, g, w.bits_out, out=Y[k])
 
@@ -318,7 +331,8 @@ def main():
                         "channels x%g, %s, group %d"
                         % (w.name, N, T, H, 100 * w.outlier_frac, w.outlier_gain,
                            "FP8 E4M3 -> FP8 E4M3 symmetric" if fp8 else
-                           "INT%d->INT%d %s" % (w.bits_in, w.bits_out, "symmetric" if sym else "asymmetric"), g)
+                           "INT%d->INT%d %s" % (w.bits_in, w.bits_out, "symmetric" if sym else
+                                                 "asymmetric, binary16 scale and zero-point" if cm else "asymmetric"), g)
                         + (", Hadamard rotation fused into quantize / dequantize" if w.rotate else ""),
             "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
             "volumes_per_step": B,
@@ -336,7 +350,7 @@ def main():
         },
         "roofline": {
             "kernel": "k_dequant_reduce_requant%s<%d,%d,%d>%s" % ("_sym" if (sym or fp8) else "", w.bits_in, w.bits_out,
-                                                                 N, " (E4M3)" if fp8 else ""),
+                                                                 N, " (E4M3)" if fp8 else " (binary16 metadata)" if cm else ""),
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,

@@ -197,6 +197,42 @@ FC_API int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, in
                                 void *y_f16, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Compact-metadata variant of the asymmetric quantizer (Eq. 1-2; the paper does not say
+ * how a group's scale and zero-point are stored or sent): both are kept in binary16, one
+ * 32-bit word per group, so a group carries 4 bytes of metadata instead of 8.
+ *   meta   uint32 [tokens, hidden/group]; bits 0-15 the scale, bits 16-31 the zero-point
+ * Other layouts and rules as for fc_quantize.  Results are bit-identical to evaluating, for
+ * every group,
+ *     s   as in fc_quantize (including the constant-group rule), then
+ *     s   = binary16_rne(s) kept inside [2^-24, 65504]  (zero -> 2^-24, overflow -> 65504)
+ *     inv = 1 / s                                 one IEEE divide, of the stored scale
+ *     z   = 0 - rint(mn * inv), then binary16_rne(z) saturated at +-65504
+ *                                                 (integers up to 2048 are unchanged)
+ *     q   = clamp(rint(x * inv) + z, 0, 2^bits - 1)
+ * Dequantize: x^ = (q - z) * s with the two stored numbers widened to fp32; ReduceSum as in
+ * fc_dequant_reduce_requant.  Input words must hold a positive finite scale and a finite
+ * zero-point.  meta_src_stride_elems counts 32-bit words.
+ */
+FC_API int fc_quantize_cmeta(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                             void *codes, uint32_t *meta, void *hip_stream);
+
+FC_API int fc_dequant_reduce_requant_cmeta(const void *codes_in, int64_t codes_src_stride_bytes,
+                                           const uint32_t *meta_in, int64_t meta_src_stride_elems,
+                                           int n_src, int64_t tokens, int64_t hidden, int group,
+                                           int bits_in, int bits_out,
+                                           void *codes_out, uint32_t *meta_out, void *hip_stream);
+
+FC_API int fc_dequantize_cmeta(const void *codes, const uint32_t *meta,
+                               int64_t tokens, int64_t hidden, int group, int bits,
+                               void *y_f16, void *hip_stream);
+
+/* Algorithm 1 end to end with binary16 metadata; workspace as for fc_allreduce_sim
+   (fc_allreduce_sim_workspace_bytes gives a sufficient size). */
+FC_API int fc_allreduce_sim_cmeta(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                                  int group, int bits_rs, int bits_ag, void *y_f16,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Rotation variant (paper Section 4, "Naive vs. Rotation-based Quantization": the Hadamard
  * transform of QuaRot around the quantized all-reduce).  Every partial is rotated before
  * the first quantization; the rotation is linear, so the unchanged

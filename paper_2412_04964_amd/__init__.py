@@ -16,19 +16,23 @@ from .binding import (  # noqa: F401
     quantize_rot,
     stream_reference,
     allreduce_sim,
+    allreduce_sim_cmeta,
     allreduce_sim_fp8,
     allreduce_sim_sym,
     allreduce_sim_workspace_bytes,
     dequant_reduce_requant,
+    dequant_reduce_requant_cmeta,
     dequant_reduce_requant_fp8,
     dequant_reduce_requant_sym,
     dequantize,
+    dequantize_cmeta,
     dequantize_fp8,
     dequantize_sym,
     last_hip_error,
     lib,
     lib_path,
     quantize,
+    quantize_cmeta,
     quantize_fp8,
     quantize_sym,
     strerror,
@@ -42,4 +46,5 @@ __all__ = [
     "dequant_reduce_requant", "dequant_reduce_requant_fp8", "dequant_reduce_requant_sym", "dequantize",
     "dequantize_fp8", "dequantize_sym", "last_hip_error", "lib", "lib_path", "quantize", "quantize_fp8",
     "quantize_sym", "strerror", "version",
+    "allreduce_sim_cmeta", "dequant_reduce_requant_cmeta", "dequantize_cmeta", "quantize_cmeta",
 ]

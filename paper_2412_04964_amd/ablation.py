@@ -35,7 +35,9 @@ def sweep(x, groups, precisions=PRECISIONS):
     power = float((exact * exact).mean())
     rows = []
     for label, (b_rs, b_ag) in precisions.items():
-        for quantizer, fn in (("asym", fc.allreduce_sim), ("sym", fc.allreduce_sim_sym)):
+        # "cmeta": the asymmetric quantizer with the scale and zero-point stored as binary16
+        for quantizer, fn in (("asym", fc.allreduce_sim), ("sym", fc.allreduce_sim_sym),
+                              ("cmeta", fc.allreduce_sim_cmeta)):
             for g in groups:
                 if x.shape[2] % g:
                     continue
@@ -79,7 +81,7 @@ def main():
           % (a.n_src, a.tokens, a.hidden))
     print("%-6s %-5s " % ("prec", "quant") + " ".join("%10s" % ("g=%d" % g) for g in groups))
     for label in ("FP8",) + tuple(PRECISIONS):
-        for q in ("asym", "sym"):
+        for q in ("asym", "cmeta", "sym"):
             r = {row["group"]: row for row in rows if row["precision"] == label and row["quantizer"] == q}
             if r:
                 print("%-6s %-5s " % (label, q) + " ".join("%10.3e" % r[g]["mse"] for g in groups))

@@ -68,6 +68,15 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize_fp8.restype = i32
         L.fc_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim_fp8.restype = i32
+        L.fc_quantize_cmeta.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        L.fc_quantize_cmeta.restype = i32
+        L.fc_dequant_reduce_requant_cmeta.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32,
+                                                      vp, vp, vp]
+        L.fc_dequant_reduce_requant_cmeta.restype = i32
+        L.fc_dequantize_cmeta.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp]
+        L.fc_dequantize_cmeta.restype = i32
+        L.fc_allreduce_sim_cmeta.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp, vp, sz, vp]
+        L.fc_allreduce_sim_cmeta.restype = i32
         L.fc_quantize_rot.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
         L.fc_quantize_rot.restype = i32
         L.fc_dequantize_rot.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp]
@@ -288,6 +297,85 @@ def allreduce_sim_sym(x, group: int, bits_rs: int, bits_ag: int, out=None, works
     _check(lib().fc_allreduce_sim_sym(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
                                       workspace.data_ptr(), workspace.numel(), _stream()),
            "fc_allreduce_sim_sym")
+    return y
+
+
+# ---- asymmetric quantizer with binary16 metadata: one 32-bit word per group ----
+# (int32 tensors: bits 0-15 the binary16 scale, bits 16-31 the binary16 zero-point)
+
+def quantize_cmeta(x, group: int, bits: int, out=None):
+    """fc_quantize_cmeta.  x: float16 [tokens, hidden] -> (codes u8 [tokens, hidden*bits/8],
+    meta i32 [tokens, hidden/group])."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    t, h = x.shape
+    if out is None:
+        if bits not in (4, 8) or group <= 0 or h % group:
+            _check(lib().fc_quantize_cmeta(None, t, h, group, bits, None, None, None), "fc_quantize_cmeta")
+        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
+        meta = torch.empty((t, h // group), dtype=torch.int32, device=x.device)
+    else:
+        codes, meta = out
+        _dev(codes, torch.uint8, "codes"); _dev(meta, torch.int32, "meta")
+    _check(lib().fc_quantize_cmeta(x.data_ptr(), t, h, group, bits, codes.data_ptr(), meta.data_ptr(),
+                                   _stream()), "fc_quantize_cmeta")
+    return codes, meta
+
+
+def dequant_reduce_requant_cmeta(codes_in, meta_in, hidden: int, group: int,
+                                 bits_in: int, bits_out: int, out=None):
+    """fc_dequant_reduce_requant_cmeta.  codes_in u8 [N, tokens, hidden*bits_in/8],
+    meta_in i32 [N, tokens, hidden/group]."""
+    torch = _torch()
+    _dev(codes_in, torch.uint8, "codes_in"); _dev(meta_in, torch.int32, "meta_in")
+    n, t = codes_in.shape[0], codes_in.shape[1]
+    if out is None:
+        if bits_out not in (4, 8) or group <= 0 or hidden % group:
+            _check(lib().fc_dequant_reduce_requant_cmeta(None, 0, None, 0, n, t, hidden, group,
+                                                         bits_in, bits_out, None, None, None),
+                   "fc_dequant_reduce_requant_cmeta")
+        codes = torch.empty((t, hidden * bits_out // 8), dtype=torch.uint8, device=codes_in.device)
+        meta = torch.empty((t, hidden // group), dtype=torch.int32, device=codes_in.device)
+    else:
+        codes, meta = out
+        _dev(codes, torch.uint8, "codes_out"); _dev(meta, torch.int32, "meta_out")
+    cstride = codes_in.stride(0) if n > 1 else 0
+    mstride = meta_in.stride(0) if n > 1 else 0
+    _check(lib().fc_dequant_reduce_requant_cmeta(
+        codes_in.data_ptr(), cstride, meta_in.data_ptr(), mstride, n, t, hidden, group, bits_in,
+        bits_out, codes.data_ptr(), meta.data_ptr(), _stream()), "fc_dequant_reduce_requant_cmeta")
+    return codes, meta
+
+
+def dequantize_cmeta(codes, meta, hidden: int, group: int, bits: int, out=None):
+    """fc_dequantize_cmeta -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(codes, torch.uint8, "codes"); _dev(meta, torch.int32, "meta")
+    t = codes.shape[0]
+    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_dequantize_cmeta(codes.data_ptr(), meta.data_ptr(), t, hidden, group, bits,
+                                     y.data_ptr(), _stream()), "fc_dequantize_cmeta")
+    return y
+
+
+def allreduce_sim_cmeta(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace=None):
+    """fc_allreduce_sim_cmeta.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    n, t, h = x.shape
+    need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
+    if need == 0 and t != 0:
+        _check(lib().fc_allreduce_sim_cmeta(None, n, t, h, group, bits_rs, bits_ag, None, None, 0, None),
+               "fc_allreduce_sim_cmeta")
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_allreduce_sim_cmeta(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
+                                        workspace.data_ptr(), workspace.numel(), _stream()),
+           "fc_allreduce_sim_cmeta")
     return y
 
 

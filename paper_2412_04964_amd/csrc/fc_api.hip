@@ -68,8 +68,10 @@ SimLayout sim_layout(int n_src, int64_t n_elems, int group, int bits_rs, int bit
     return L;
 }
 
-// All quantizer variants share these; every codec but the asymmetric one drops
-// the zero-point arrays (passed as nullptr to the launchers).
+// All quantizer variants share these; every codec but the fp32-metadata asymmetric
+// one drops the zero-point arrays (passed as nullptr to the launchers).  The
+// binary16-metadata codec passes its array of 32-bit words where the others pass
+// `scales`: the kernels move those words as raw bits.
 int quantize_impl(int codec, const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                   void *codes, float *scales, float *zeros, void *hip_stream)
 {
@@ -345,6 +347,39 @@ int fc_allreduce_sim_fp8(const void *x_f16, int n_src, int64_t tokens, int64_t h
                               workspace, workspace_bytes, hip_stream);
 }
 
+int fc_quantize_cmeta(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
+                      void *codes, uint32_t *meta, void *hip_stream)
+{
+    return quantize_impl(fc::CODEC_ASYMH, x_f16, tokens, hidden, group, bits, codes,
+                         reinterpret_cast<float *>(meta), nullptr, hip_stream);
+}
+
+int fc_dequant_reduce_requant_cmeta(const void *codes_in, int64_t codes_src_stride_bytes,
+                                    const uint32_t *meta_in, int64_t meta_src_stride_elems,
+                                    int n_src, int64_t tokens, int64_t hidden, int group,
+                                    int bits_in, int bits_out,
+                                    void *codes_out, uint32_t *meta_out, void *hip_stream)
+{
+    return fused_impl(fc::CODEC_ASYMH, codes_in, codes_src_stride_bytes, reinterpret_cast<const float *>(meta_in),
+                      nullptr, meta_src_stride_elems, n_src, tokens, hidden, group, bits_in, bits_out, codes_out,
+                      reinterpret_cast<float *>(meta_out), nullptr, hip_stream);
+}
+
+int fc_dequantize_cmeta(const void *codes, const uint32_t *meta, int64_t tokens, int64_t hidden, int group,
+                        int bits, void *y_f16, void *hip_stream)
+{
+    return dequantize_impl(fc::CODEC_ASYMH, codes, reinterpret_cast<const float *>(meta), nullptr, tokens, hidden,
+                           group, bits, y_f16, hip_stream);
+}
+
+int fc_allreduce_sim_cmeta(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                           int group, int bits_rs, int bits_ag, void *y_f16,
+                           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return allreduce_sim_impl(fc::CODEC_ASYMH, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+                              workspace, workspace_bytes, hip_stream);
+}
+
 int fc_quantize_rot(const void *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                     int quantizer, void *codes, float *scales, float *zeros, void *hip_stream)
 {
@@ -424,7 +459,7 @@ const char *fc_strerror(int code)
     case FC_OK: return "success";
     case FC_ERR_NULL: return "a required pointer is NULL";
     case FC_ERR_BITS: return "bit-width must be 4 or 8";
-    case FC_ERR_GROUP: return "group must be a power of two in [32, 1024] that divides hidden";
+    case FC_ERR_GROUP: return "group must be a power of two in [32, 16384] that divides hidden";
     case FC_ERR_SHAPE: return "bad tokens / hidden / n_src / source stride";
     case FC_ERR_ALIGN: return "pointers and strides must be 16-byte aligned";
     case FC_ERR_WORKSPACE: return "workspace missing or too small";

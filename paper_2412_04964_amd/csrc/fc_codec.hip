@@ -15,6 +15,8 @@ static void launch_q(int codec, hipStream_t stream, const uint16_t *x, int64_t n
         k_quantize<BITS, LPG, kAsym><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, zeros);
     else if (codec == CODEC_SYM)
         k_quantize<BITS, LPG, kSym><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, nullptr);
+    else if (codec == CODEC_ASYMH)
+        k_quantize<BITS, LPG, kAsymH><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, nullptr);
     else if constexpr (BITS == 8)
         k_quantize<8, LPG, kFp8><<<grid, block, 0, stream>>>(x, n_elems, lpg, group_shift, c, scales, nullptr);
 }
@@ -59,6 +61,11 @@ hipError_t launch_dequantize(int bits, int codec, const void *codes, const float
     if (codec == CODEC_FP8) {
         if (bits != 8) return hipErrorInvalidValue;
         k_dequantize<8, kFp8><<<grid, block, 0, stream>>>(c, scales, nullptr, n_elems, sh, y);
+    } else if (codec == CODEC_ASYMH) {
+        if (bits == 4)
+            k_dequantize<4, kAsymH><<<grid, block, 0, stream>>>(c, scales, nullptr, n_elems, sh, y);
+        else
+            k_dequantize<8, kAsymH><<<grid, block, 0, stream>>>(c, scales, nullptr, n_elems, sh, y);
     } else if (bits == 4 && codec == CODEC_ASYM)
         k_dequantize<4, kAsym><<<grid, block, 0, stream>>>(c, scales, zeros, n_elems, sh, y);
     else if (bits == 4)

@@ -44,6 +44,8 @@ constexpr int kBlockWaves = kBlockThreads / 64;
 constexpr int kAsym = 0;    // Eq. 1-2: unsigned codes, scale and zero-point
 constexpr int kSym = 1;     // Eq. 3-4: signed codes, scale only
 constexpr int kFp8 = 2;     // FP8 E4M3 bytes, scale only (8-bit only)
+constexpr int kAsymH = 3;   // Eq. 1-2 with the scale and zero-point stored as binary16, one 32-bit word per group
+constexpr bool is_asym(int codec) { return codec == kAsym || codec == kAsymH; }
 
 // elements per lane for a given code width: one 128-bit access of codes
 constexpr int lane_elems(int bits) { return 128 / bits; }
@@ -228,7 +230,12 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lpg_rt)
 //       below FLT_MIN here, and a wavefront holding an s above 2^100 takes the
 //       ordinary division.
 // ---------------------------------------------------------------------------
-template <int BITS>
+//
+// HM (binary16 metadata): the scale is rounded to binary16 (nearest even, kept in
+// [2^-24, 65504]) before the reciprocal is taken, so that the zero-point and every
+// code are computed from the number that is stored; the zero-point is then rounded
+// to binary16 as well (saturating at +-65504; integers up to 2048 are unchanged).
+template <int BITS, bool HM = false>
 __device__ __forceinline__ void group_params(float mn, float mx, float &s, float &inv, float &zf)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
@@ -241,14 +248,40 @@ __device__ __forceinline__ void group_params(float mn, float mx, float &s, float
         const float a = fabsf(mn);
         s = (a >= FLT_MIN) ? a : 1.0f;
     }
-    if (__builtin_amdgcn_ballot_w64(!(s <= 0x1p100f)) == 0) {
+    if constexpr (HM) s = (float)(_Float16)__builtin_amdgcn_fmed3f(s, 0x1p-24f, 65504.0f);
+    if (HM || __builtin_amdgcn_ballot_w64(!(s <= 0x1p100f)) == 0) {
         const float y0 = __builtin_amdgcn_rcpf(s);
         const float e1 = fmaf(-s, y0, 1.0f);
         inv = fmaf(e1, y0, y0);            // == 1 / s
     } else {
         inv = 1.0f / s;
     }
-    zf = 0.0f - rintf(mn * inv);
+    float t = rintf(mn * inv);
+    if constexpr (HM) t = __builtin_amdgcn_fmed3f(t, -65504.0f, 65504.0f);
+    zf = 0.0f - t;
+    if constexpr (HM) {
+        // The difference is pinned in a register first: feeding it straight into the conversion lets
+        // the compiler replace "0 - t" by a negation modifier on the operand, which turns the +0 that
+        // a group starting at zero must store into -0.
+        asm volatile("" : "+v"(zf));
+        zf = (float)(_Float16)zf;
+    }
+}
+
+// the metadata word of the binary16 variant: scale in bits 0-15, zero-point in bits 16-31
+__device__ __forceinline__ u32 pack_meta(float s, float zf)
+{
+    h2 m;
+    m.x = (_Float16)s;                     // both are binary16 numbers already
+    m.y = (_Float16)zf;
+    return as_u32(m);
+}
+
+__device__ __forceinline__ void unpack_meta(u32 w, float &s, float &zf)
+{
+    const h2 m = as_h2(w);
+    s = (float)m.x;
+    zf = (float)m.y;
 }
 
 // Eq. 2 for one element; returns the code as an integer in [0, 2^BITS-1].
@@ -349,7 +382,7 @@ __device__ __forceinline__ void lane_minmax(const float (&v)[EPL], float &mn, fl
     }
 }
 
-template <int BITS, int EPL, int LPG>
+template <int BITS, int EPL, int LPG, bool HM = false>
 __device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
                                               u32 (&word)[EPL * BITS / 32], float &s, float &zf)
 {
@@ -357,7 +390,7 @@ __device__ __forceinline__ void quantize_lane(const float (&v)[EPL], int lpg_rt,
     lane_minmax(v, mn, mx);
     group_minmax<LPG>(mn, mx, lpg_rt);
     float inv;
-    group_params<BITS>(mn, mx, s, inv, zf);
+    group_params<BITS, HM>(mn, mx, s, inv, zf);
     pack_lane<BITS, EPL>(v, inv, zf, mx, word);
 }
 
@@ -380,7 +413,7 @@ __device__ __forceinline__ void cross_wave_minmax(float &mn, float &mx, float (*
 }
 
 // quantize_lane for a run-time group width of 16 ... 256 lanes (up to the whole workgroup)
-template <int BITS, int EPL>
+template <int BITS, int EPL, bool HM = false>
 __device__ __forceinline__ void quantize_lane_any(const float (&v)[EPL], int lpg, float (*slot)[2],
                                                   u32 wave, u32 lane,
                                                   u32 (&word)[EPL * BITS / 32], float &s, float &zf)
@@ -390,7 +423,7 @@ __device__ __forceinline__ void quantize_lane_any(const float (&v)[EPL], int lpg
     group_minmax<0>(mn, mx, lpg);
     if (lpg > 64) cross_wave_minmax(mn, mx, slot, wave, lane, (u32)lpg >> 6);
     float inv;
-    group_params<BITS>(mn, mx, s, inv, zf);
+    group_params<BITS, HM>(mn, mx, s, inv, zf);
     pack_lane<BITS, EPL>(v, inv, zf, mx, word);
 }
 
@@ -791,7 +824,8 @@ __device__ __forceinline__ void accumulate_general(const u32 (&w)[4], float s, f
 // One tile of BT*EPL elements per workgroup.  The wavefront's 64*EPL*2 input
 // bytes are fetched as coalesced 1 KB pieces straight into LDS (an image of
 // global memory) and each lane then reads its EPL contiguous values from there.
-// CODEC selects the quantizer (`zeros` is used by kAsym only).
+// CODEC selects the quantizer (`zeros` is used by kAsym only; with kAsymH `scales`
+// is the array of 32-bit metadata words).
 template <int BITS, int LPG, int CODEC>
 __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
     const uint16_t *__restrict__ x, int64_t n_elems, int lpg, int group_shift,
@@ -836,12 +870,12 @@ __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
     else if constexpr (CODEC == kSym)
         quantize_lane_sym<BITS, EPL, LPG>(v, lpg, word, s);
     else
-        quantize_lane<BITS, EPL, LPG>(v, lpg, word, s, zf);
+        quantize_lane<BITS, EPL, LPG, CODEC == kAsymH>(v, lpg, word, s, zf);
     store_codes<16>(word, rc, wave, lane, nullptr);
     const int lpg_v = LPG > 0 ? LPG : lpg;
     if ((tid & (lpg_v - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
-        store_f32(rs, gi * 4, s);
+        store_f32(rs, gi * 4, CODEC == kAsymH ? __builtin_bit_cast(float, pack_meta(s, zf)) : s);
         if constexpr (CODEC == kAsym) store_f32(rz, gi * 4, zf);
     }
 }
@@ -859,7 +893,9 @@ __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
 // ds_read_b128 per lane (conflict-free) as soon as its load has retired.
 // The group scales / zero-points reach the lanes in one of two ways, chosen at
 // compile time by the group width (see kDirectMeta below).
-template <int BITS_IN, int BITS_OUT, int NSRC, int LPG>
+// HM = true: binary16 metadata; scales_in / scales_out are the arrays of 32-bit
+// metadata words and the zeros arrays are not used.
+template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool HM = false>
 __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_requant(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, const float *__restrict__ zeros_in, int64_t meta_stride,
@@ -910,7 +946,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 #pragma unroll
         for (int j = 0; j < NSRC; ++j) {
             ms_[j] = scales_in[(int64_t)j * meta_stride + g_lane];
-            mz_[j] = zeros_in[(int64_t)j * meta_stride + g_lane];
+            if constexpr (!HM) mz_[j] = zeros_in[(int64_t)j * meta_stride + g_lane];
         }
         issue_order_fence();
 #pragma unroll
@@ -920,6 +956,10 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
             dma_piece(rc, tid * 16, &landing[wave][j][0]);
         }
         issue_order_fence();
+        if constexpr (HM) {
+#pragma unroll
+            for (int j = 0; j < NSRC; ++j) unpack_meta(__builtin_bit_cast(u32, ms_[j]), ms_[j], mz_[j]);
+        }
         bool ok = true;
 #pragma unroll
         for (int j = 0; j < NSRC; ++j) ok = ok && zero_is_fast(mz_[j]);
@@ -943,7 +983,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
             gi = gi < n_groups ? gi : n_groups - 1;               // ragged tail: stay inside the array
             const int64_t at = (int64_t)j * meta_stride + gi;
             ms[it] = scales_in[at];
-            mz[it] = zeros_in[at];
+            if constexpr (!HM) mz[it] = zeros_in[at];
         }
         issue_order_fence();
 
@@ -957,6 +997,10 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
         issue_order_fence();
 
         // --- table: check, convert, publish
+        if constexpr (HM) {
+#pragma unroll
+            for (int it = 0; it < K; ++it) unpack_meta(__builtin_bit_cast(u32, ms[it]), ms[it], mz[it]);
+        }
         bool ok = true;
 #pragma unroll
         for (int it = 0; it < K; ++it) ok = ok && zero_is_fast(mz[it]);
@@ -1009,17 +1053,17 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     u32 word[EPL * BITS_OUT / 32];
     float s, zf;
     if constexpr (LPG == 0)
-        quantize_lane_any<BITS_OUT, EPL>(acc, lpg, slot, wave, lane, word, s, zf);
+        quantize_lane_any<BITS_OUT, EPL, HM>(acc, lpg, slot, wave, lane, word, s, zf);
     else
-        quantize_lane<BITS_OUT, EPL, LPG>(acc, lpg, word, s, zf);
+        quantize_lane<BITS_OUT, EPL, LPG, HM>(acc, lpg, word, s, zf);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
-    const rsrc_t rz = make_rsrc(zeros_out + g_tile, (n_groups - g_tile) * 4);
+    const rsrc_t rz = make_rsrc(HM ? scales_out + g_tile : zeros_out + g_tile, (n_groups - g_tile) * 4);
     store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
     if ((tid & (lpg_v - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
-        store_f32(rs, gi * 4, s);
-        store_f32(rz, gi * 4, zf);
+        store_f32(rs, gi * 4, HM ? __builtin_bit_cast(float, pack_meta(s, zf)) : s);
+        if constexpr (!HM) store_f32(rz, gi * 4, zf);
     }
 }
 
@@ -1106,6 +1150,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 }
 
 // Dequantize to binary16 (Algorithm 1, last step): y = half_rne((q - z) * s).
+// With kAsymH `scales` is the array of 32-bit metadata words.
 // One tile of 256*EPL elements per workgroup; the EPL halves of a lane are laid
 // out in the wavefront's LDS image and leave as coalesced 1 KB pieces.
 template <int BITS, int CODEC>
@@ -1127,7 +1172,8 @@ __global__ FC_KERNEL_ATTRS void k_dequantize(
     const rsrc_t rz = make_rsrc(CODEC != kAsym ? scales + g_tile : zeros + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t ry = make_rsrc(y + e_tile, (n_elems - e_tile) * 2);
 
-    const float s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
+    const float s_raw = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
+    float s = s_raw;
     const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamPolicy);
 
     float d[EPL];
@@ -1139,7 +1185,11 @@ __global__ FC_KERNEL_ATTRS void k_dequantize(
                           to_offset_binary<BITS>(a[2]), to_offset_binary<BITS>(a[3])};
         codes_minus_zero_fast<BITS>(w, sym_zero_const<BITS>(), d);
     } else {
-        const float zf = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rz, gi * 4, 0, 0));
+        float zf;
+        if constexpr (CODEC == kAsymH)
+            unpack_meta(__builtin_bit_cast(u32, s_raw), s, zf);
+        else
+            zf = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rz, gi * 4, 0, 0));
         const u32 w[4] = {a[0], a[1], a[2], a[3]};
         const bool wave_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0;
         if (wave_fast)

@@ -37,6 +37,14 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
         return hipGetLastError();
     }
+    if (a.codec == CODEC_ASYMH) {
+        k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, true>
+            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
+                static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, nullptr,
+                a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                static_cast<uint8_t *>(a.codes_out), a.scales_out, nullptr);
+        return hipGetLastError();
+    }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
         <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(

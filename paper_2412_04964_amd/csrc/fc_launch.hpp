@@ -7,9 +7,11 @@
 
 namespace fc {
 
-// Quantizer: 0 = asymmetric (Eq. 1-2), 1 = symmetric (Eq. 3-4), 2 = FP8 E4M3 (8 bit only);
-// the values match kAsym / kSym / kFp8 of the device code.  Only codec 0 uses zero-points.
-enum { CODEC_ASYM = 0, CODEC_SYM = 1, CODEC_FP8 = 2 };
+// Quantizer: 0 = asymmetric (Eq. 1-2), 1 = symmetric (Eq. 3-4), 2 = FP8 E4M3 (8 bit only),
+// 3 = asymmetric with binary16 metadata (one 32-bit word per group, passed where the other
+// codecs pass `scales`); the values match kAsym / kSym / kFp8 / kAsymH of the device code.
+// Only codec 0 uses the zero-point arrays.
+enum { CODEC_ASYM = 0, CODEC_SYM = 1, CODEC_FP8 = 2, CODEC_ASYMH = 3 };
 
 // n_elems = tokens*hidden (a multiple of `group`, which is a power of two in
 // [32, 16384]).  All pointers are device pointers.

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
     else if constexpr (CODEC == kSym)
         group_params_sym<BITS>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);   // max|x| = max(|min|, |max|)
     else
-        group_params<BITS>(mn, mx, s, inv, zf);
+        group_params<BITS, CODEC == kAsymH>(mn, mx, s, inv, zf);
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         u32 word[EPL * BITS / 32];
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
                                                (p * blockDim.x + tid) * 16, 0, kStreamPolicy);
     }
     if (tid == 0) {
-        scales[blockIdx.x] = s;
+        scales[blockIdx.x] = CODEC == kAsymH ? __builtin_bit_cast(float, pack_meta(s, zf)) : s;
         if constexpr (CODEC == kAsym) zeros[blockIdx.x] = zf;
     }
 }
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
         for (int d = 0; d < D; ++d)
             if (j0 + d < n_src) {
                 const int j = j0 + d;
-                const float s = scales_in[(int64_t)j * meta_stride + g_idx];
+                float s = scales_in[(int64_t)j * meta_stride + g_idx];
                 if constexpr (CODEC == kFp8) {
 #pragma unroll
                     for (int p = 0; p < P; ++p) {
@@ -173,7 +173,11 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
                         accumulate_fast<BITS_IN>(w, s, zc, acc[p]);
                     }
                 } else {
-                    const float zf = zeros_in[(int64_t)j * meta_stride + g_idx];
+                    float zf;
+                    if constexpr (CODEC == kAsymH)
+                        unpack_meta(__builtin_bit_cast(u32, s), s, zf);
+                    else
+                        zf = zeros_in[(int64_t)j * meta_stride + g_idx];
                     const bool fast = zero_is_fast(zf);       // uniform over the workgroup
                     const ZeroConst zc = unpack_zero_const(pack_zero_const(fast ? zf : 0.0f));
 #pragma unroll
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
     else if constexpr (CODEC == kSym)
         group_params_sym<BITS_OUT>(fmaxf(fabsf(mn), fabsf(mx)), s, inv);
     else
-        group_params<BITS_OUT>(mn, mx, s, inv, zf);
+        group_params<BITS_OUT, CODEC == kAsymH>(mn, mx, s, inv, zf);
 
     const int64_t out_bytes = (int64_t)group * BITS_OUT / 8;
     const u32 sub_out = blockDim.x * kOutBytes;               // output bytes of one sub-tile
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
         store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
     }
     if (tid == 0) {
-        scales_out[g_idx] = s;
+        scales_out[g_idx] = CODEC == kAsymH ? __builtin_bit_cast(float, pack_meta(s, zf)) : s;
         if constexpr (CODEC == kAsym) zeros_out[g_idx] = zf;
     }
 }
@@ -314,6 +318,9 @@ hipError_t launch_quantize_wide(int bits, int codec, const void *x_f16, int64_t 
     if (codec == CODEC_FP8)
         return bits == 8 ? quantize_wide_bits<8, kFp8>(x, n_elems, group, c, scales, nullptr, stream)
                          : hipErrorInvalidValue;
+    if (codec == CODEC_ASYMH)
+        return bits == 4 ? quantize_wide_bits<4, kAsymH>(x, n_elems, group, c, scales, nullptr, stream)
+                         : quantize_wide_bits<8, kAsymH>(x, n_elems, group, c, scales, nullptr, stream);
     if (bits == 4)
         return codec == CODEC_ASYM ? quantize_wide_bits<4, kAsym>(x, n_elems, group, c, scales, zeros, stream)
                                    : quantize_wide_bits<4, kSym>(x, n_elems, group, c, scales, nullptr, stream);
@@ -325,6 +332,11 @@ hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipS
 {
     if (a.codec == CODEC_FP8)
         return (bits_in == 8 && bits_out == 8) ? fused_wide_bits<8, 8, kFp8>(a, stream) : hipErrorInvalidValue;
+    if (a.codec == CODEC_ASYMH) {
+        if (bits_in == 4)
+            return bits_out == 4 ? fused_wide_bits<4, 4, kAsymH>(a, stream) : fused_wide_bits<4, 8, kAsymH>(a, stream);
+        return bits_out == 4 ? fused_wide_bits<8, 4, kAsymH>(a, stream) : fused_wide_bits<8, 8, kAsymH>(a, stream);
+    }
     const bool sym = a.codec == CODEC_SYM;
     if (bits_in == 4 && bits_out == 4)
         return sym ? fused_wide_bits<4, 4, kSym>(a, stream) : fused_wide_bits<4, 4, kAsym>(a, stream);

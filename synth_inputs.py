@@ -31,7 +31,8 @@ class Workload:
     outlier_gain: float = 20.0
     seed: int = 0
     quantizer: str = "asym"   # "asym": Eq. 1-2 (scale + zero-point), "sym": Eq. 3-4 (scale only),
-                              # "fp8": E4M3 bytes with a per-group scale (the paper's FP8_Sym rows)
+                              # "fp8": E4M3 bytes with a per-group scale (the paper's FP8_Sym rows),
+                              # "cmeta": Eq. 1-2 with the scale and zero-point stored as binary16 (4 bytes)
 
     rotate: bool = False      # Hadamard rotation around the all-reduce (Section 4 of the paper)
 
@@ -63,6 +64,8 @@ WORKLOADS = {
                                                  rotate=True),
     "llama3_70b_prefill_rot": Workload("llama3_70b_prefill_rot", 4, 8192, 8192, 4, 4, 128, rotate=True),
     "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
+    "llama3_70b_prefill_cmeta": Workload("llama3_70b_prefill_cmeta", 4, 8192, 8192, 4, 4, 128, quantizer="cmeta"),
+    "llama3_8b_prefill_cmeta": Workload("llama3_8b_prefill_cmeta", 4, 8192, 4096, 8, 8, 128, quantizer="cmeta"),
 }
 
 

@@ -134,6 +134,19 @@ def test_variant_entry_points_argument_checks(L):
     need = L.fc_allreduce_sim_workspace_bytes(4, 16, 4096, 128, 8, 8)
     assert L.fc_allreduce_sim_fp8(P, 4, 16, 4096, 128, P, P, need - 1, None) == -6
     assert L.fc_allreduce_sim_sym(P, 4, 16, 4096, 128, 4, 4, P, None, need, None) == -6
+    # binary16 metadata: one array of 32-bit words in place of scales and zero-points
+    assert L.fc_quantize_cmeta(P, 4, 256, 128, 5, P, P, None) == -2
+    assert L.fc_quantize_cmeta(P, 4, 256, 128, 4, P, None, None) == -1
+    assert L.fc_quantize_cmeta(P, 4, 256, 128, 4, P, P + 4, None) == -5
+    assert L.fc_quantize_cmeta(P, 4, 256, 48, 4, P, P, None) == -3
+    assert L.fc_quantize_cmeta(None, 0, 256, 128, 4, None, None, None) == 0
+    assert L.fc_dequant_reduce_requant_cmeta(P, cs // 2, P, 7, 4, 4, 256, 128, 4, 4, P, P, None) == -4
+    assert L.fc_dequant_reduce_requant_cmeta(P, cs // 2, None, 8, 4, 4, 256, 128, 4, 4, P, P, None) == -1
+    assert L.fc_dequant_reduce_requant_cmeta(P, cs // 2, P, 8, 4, 4, 256, 128, 4, 6, P, P, None) == -2
+    assert L.fc_dequantize_cmeta(P, None, 4, 256, 128, 4, P, None) == -1
+    need44 = L.fc_allreduce_sim_workspace_bytes(4, 16, 4096, 128, 4, 4)
+    assert L.fc_allreduce_sim_cmeta(P, 4, 16, 4096, 128, 4, 4, P, P, need44 - 1, None) == -6
+    assert L.fc_allreduce_sim_cmeta(P, 9, 16, 4096, 128, 4, 4, P, P, need, None) == -4
 
 
 def test_rotation_and_stream_reference_argument_checks(L):

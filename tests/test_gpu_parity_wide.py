@@ -141,14 +141,15 @@ def test_ablation_sweep_matches_oracle_errors(fc):
     from paper_2412_04964_amd import ablation
     x = synth_inputs.make_partials(4, 8, 4096, seed=6)
     rows = ablation.sweep(dev(x.view(np.uint16)).view(torch.float16), [128, 1024, 4096])
-    assert len(rows) == 3 * 2 * 3 + 3
+    assert len(rows) == 3 * 3 * 3 + 3
     exact = x.astype(np.float64).sum(0)
     for r in rows:
         if r["precision"] == "FP8":
             y = oracle.allreduce_sim_fp8(x, r["group"])
         else:
             b_rs, b_ag = ablation.PRECISIONS[r["precision"]]
-            fn = oracle.allreduce_sim_sym if r["quantizer"] == "sym" else oracle.allreduce_sim
+            fn = {"sym": oracle.allreduce_sim_sym, "cmeta": oracle.allreduce_sim_cmeta,
+                  "asym": oracle.allreduce_sim}[r["quantizer"]]
             y = fn(x, r["group"], b_rs, b_ag)
         want = float(np.mean((y.astype(np.float64) - exact) ** 2))
         assert abs(r["mse"] - want) <= 1e-4 * want, r
