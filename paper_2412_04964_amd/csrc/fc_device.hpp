@@ -156,9 +156,13 @@ __device__ __forceinline__ void pin_values(float (&v)[N])
 // which streams measurably faster for the many-streams-in, one-stream-out
 // pattern of the fused kernel than interleaving the XCDs tile by tile (the
 // one-in, one-out codec kernels gain nothing from it and keep the plain order).
-__device__ __forceinline__ u32 xcd_tile()
+// n = number of workgroups of the launch.  The callers derive it from the volume instead of reading
+// gridDim: the explicit kernel arguments are preloaded into scalar registers at wavefront start (see
+// the build flags) while gridDim would cost a memory read before the first load can be issued, and
+// these short-lived wavefronts are sensitive to that delay (1 % of the fused kernel's time).
+__device__ __forceinline__ u32 xcd_tile(u32 n)
 {
-    const u32 b = blockIdx.x, n = gridDim.x;
+    const u32 b = blockIdx.x;
     return (n & 7u) == 0 ? (b & 7u) * (n >> 3) + (b >> 3) : b;
 }
 
@@ -924,7 +928,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     const int gw_shift = __builtin_ctz(gw);
     const int entries = NSRC * gw;
 
-    const u32 tile = xcd_tile();
+    const u32 tile = xcd_tile((u32)((n_elems + kTileElems - 1) / kTileElems));
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
 
@@ -1092,7 +1096,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
     const int lpg_v = LPG > 0 ? LPG : lpg;
-    const u32 tile = xcd_tile();
+    const u32 tile = xcd_tile((u32)((n_elems + kTileElems - 1) / kTileElems));
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
     const u32 gi = (tid * EPL) >> group_shift;
@@ -1229,7 +1233,8 @@ __global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(con
 {
     __shared__ __attribute__((aligned(16))) uint8_t landing[fused_block_threads(1) / 64][NSRC][1024];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const int64_t b_tile = (int64_t)xcd_tile() * (fused_block_threads(1) * 16);
+    constexpr int kTileBytes = fused_block_threads(1) * 16;
+    const int64_t b_tile = (int64_t)xcd_tile((u32)((bytes + kTileBytes - 1) / kTileBytes)) * kTileBytes;
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) {
         const rsrc_t r = make_rsrc(in + (int64_t)j * in_stride + b_tile, bytes - b_tile);
