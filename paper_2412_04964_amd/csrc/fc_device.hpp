@@ -1,7 +1,7 @@
 // fc_device.hpp -- gfx950 device code of the Flash Communication quantization
 // path: the group quantizers (paper Appendix, Eq. 1-2 asymmetric, Eq. 3-4
-// symmetric, and the FP8 E4M3 variant of the paper's precision table), their
-// inverses, and the fused Dequantize x N -> ReduceSum -> FinegrainedQuantize body
+// symmetric, the FP8 E4M3 variant of the paper's precision table, and Eq. 1-2
+// with binary16 metadata), their inverses, and the fused Dequantize x N -> ReduceSum -> FinegrainedQuantize body
 // of Algorithm 1.  Groups wider than this file's kernels handle and the Hadamard
 // rotation are in fc_wide.hip and fc_rot.hip, built from the same functions.
 //
@@ -37,8 +37,6 @@ namespace fc {
 
 constexpr int kBlockThreads = 256;                   // 4 wavefronts
 constexpr int kBlockWaves = kBlockThreads / 64;
-
-#define FC_KERNEL_ATTRS __launch_bounds__(kBlockThreads)
 
 // quantizer selected by a template argument of the kernels
 constexpr int kAsym = 0;    // Eq. 1-2: unsigned codes, scale and zero-point
@@ -1158,7 +1156,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 // One tile of 256*EPL elements per workgroup; the EPL halves of a lane are laid
 // out in the wavefront's LDS image and leave as coalesced 1 KB pieces.
 template <int BITS, int CODEC>
-__global__ FC_KERNEL_ATTRS void k_dequantize(
+__global__ __launch_bounds__(kBlockThreads) void k_dequantize(
     const uint8_t *__restrict__ codes, const float *__restrict__ scales,
     const float *__restrict__ zeros, int64_t n_elems, int group_shift, uint16_t *__restrict__ y)
 {
