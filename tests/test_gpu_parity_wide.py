@@ -226,6 +226,70 @@ def test_large_volume_offsets_beyond_32_bits(fc):
     assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), "large volume output"
 
 
+@pytest.mark.parametrize("variant", ["sym", "fp8", "cmeta"])
+def test_large_volume_other_quantizers(fc, variant):
+    # 2^32 + 24576 elements through the symmetric, FP8 and compact-metadata kernels at 8 bit: element
+    # indices and the byte offsets of the input and of the codes all pass 2^32 inside the volume
+    hidden, group, bits = 8192, 128, 8
+    tokens = (1 << 19) + 3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * (1 << 30):
+        pytest.skip("needs 60 GB of free device memory")
+    g = torch.Generator(device="cuda"); g.manual_seed(9)
+    x = torch.empty((2, tokens, hidden), dtype=torch.float16, device="cuda")
+    chunk = 1 << 16
+    for r0 in range(0, tokens, chunk):
+        r1 = min(tokens, r0 + chunk)
+        x[0, r0:r1] = (torch.randn((r1 - r0, hidden), generator=g, device="cuda") * (1.0 + (r0 // chunk) % 3)).half()
+    x[1] = x[0].flip(1)
+    if variant == "sym":
+        q = lambda t, out: fc.quantize_sym(t, group, bits, out=out)
+        f = lambda c, m: fc.dequant_reduce_requant_sym(c, m, hidden, group, bits, bits)
+        d = lambda c, m: fc.dequantize_sym(c, m, hidden, group, bits)
+        oq = lambda a: oracle.quantize_sym(a, group, bits)
+        of = lambda c, m: oracle.dequant_reduce_requant_sym(c, m, hidden, group, bits, bits)
+        od = lambda c, m: oracle.dequantize_sym(c, m, hidden, group, bits)
+        mdt = torch.float32
+    elif variant == "fp8":
+        q = lambda t, out: fc.quantize_fp8(t, group, out=out)
+        f = lambda c, m: fc.dequant_reduce_requant_fp8(c, m, hidden, group)
+        d = lambda c, m: fc.dequantize_fp8(c, m, hidden, group)
+        oq = lambda a: oracle.quantize_fp8(a, group)
+        of = lambda c, m: oracle.dequant_reduce_requant_fp8(c, m, hidden, group)
+        od = lambda c, m: oracle.dequantize_fp8(c, m, hidden, group)
+        mdt = torch.float32
+    else:
+        q = lambda t, out: fc.quantize_cmeta(t, group, bits, out=out)
+        f = lambda c, m: fc.dequant_reduce_requant_cmeta(c, m, hidden, group, bits, bits)
+        d = lambda c, m: fc.dequantize_cmeta(c, m, hidden, group, bits)
+        oq = lambda a: oracle.quantize_cmeta(a, group, bits)
+        of = lambda c, m: oracle.dequant_reduce_requant_cmeta(c, m.view(np.uint32), hidden, group, bits, bits)
+        od = lambda c, m: oracle.dequantize_cmeta(c, m.view(np.uint32), hidden, group, bits)
+        mdt = torch.int32
+    c = torch.empty((2, tokens, hidden), dtype=torch.uint8, device="cuda")
+    m = torch.empty((2, tokens, hidden // group), dtype=mdt, device="cuda")
+    for j in range(2):
+        q(x[j], (c[j], m[j]))
+    co, mo = f(c, m)
+    y = d(co, mo)
+    torch.cuda.synchronize()
+    marks = [0, 1, (1 << 32) // hidden - 1, (1 << 32) // hidden, (1 << 31) // hidden, (1 << 18) + 1,
+             tokens - 3, tokens - 2, tokens - 1]
+    rows = np.unique(np.array(marks + list(np.random.default_rng(8).integers(0, tokens, 16))))
+    ridx = torch.from_numpy(rows).cuda()
+    bits_of = lambda a: np.ascontiguousarray(a).view(np.uint32) if a.dtype != np.uint8 else a
+    ref = [oq(x[j, ridx].cpu().numpy()) for j in range(2)]
+    for j in range(2):
+        assert same_bits(c[j, ridx].cpu().numpy(), ref[j][0]), "%s stage 1 codes, source %d" % (variant, j)
+        assert same_bits(bits_of(m[j, ridx].cpu().numpy()), bits_of(ref[j][1])), "%s stage 1 meta, source %d" % (variant, j)
+    rc = np.stack([r[0] for r in ref]); rm = np.stack([bits_of(r[1]) for r in ref]).view(ref[0][1].dtype)
+    want = of(rc, rm)
+    assert same_bits(co[ridx].cpu().numpy(), want[0]), variant + " fused codes"
+    assert same_bits(bits_of(mo[ridx].cpu().numpy()), bits_of(want[1])), variant + " fused meta"
+    wy = od(*want)
+    assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), variant + " output"
+
+
 @pytest.mark.parametrize("kind", range(synth_inputs.STRESS_KINDS))
 def test_value_distributions_end_to_end(fc, kind):
     # every quantizer and the rotation, end to end, on value distributions that reach the corners
