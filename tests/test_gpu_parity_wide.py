@@ -140,11 +140,18 @@ def test_ablation_sweep_matches_oracle_errors(fc):
     # the error table of the granularity / precision sweep equals what the oracle's outputs give
     from paper_2412_04964_amd import ablation
     x = synth_inputs.make_partials(4, 8, 4096, seed=6)
-    rows = ablation.sweep(dev(x.view(np.uint16)).view(torch.float16), [128, 1024, 4096])
-    assert len(rows) == 3 * 3 * 3 + 3
+    rows = ablation.sweep(dev(x.view(np.uint16)).view(torch.float16), [128, 1024, 4096], rotation=True)
+    assert len(rows) == (3 * 3 * 3 + 3) + (3 * 2 * 3 + 3)
     exact = x.astype(np.float64).sum(0)
     for r in rows:
-        if r["precision"] == "FP8":
+        if r["quantizer"].endswith("+ht"):
+            if r["precision"] == "FP8":
+                y = oracle.allreduce_sim_rot(x, r["group"], 8, 8, oracle.FP8)
+            else:
+                b_rs, b_ag = ablation.PRECISIONS[r["precision"]]
+                y = oracle.allreduce_sim_rot(x, r["group"], b_rs, b_ag,
+                                             oracle.SYM if r["quantizer"] == "sym+ht" else oracle.ASYM)
+        elif r["precision"] == "FP8":
             y = oracle.allreduce_sim_fp8(x, r["group"])
         else:
             b_rs, b_ag = ablation.PRECISIONS[r["precision"]]
