@@ -334,7 +334,7 @@ __device__ __forceinline__ void pack_codes(const float (&v)[EPL], float inv, flo
 // FinegrainedQuantize of the lane's EPL fp32 values: packed code words plus the
 // group's scale and zero-point (identical in all lanes of the group).
 //
-// Packing, fast path (|z| <= 2048 in every lane of the wavefront): with
+// Packing, fast path (|z| < 2048 in every lane of the wavefront): with
 // t = rint(x*inv) the code is q = clamp(t + z, 0, qmax).  t >= rint(mn*inv) = -z
 // because x >= mn and both the product and rint are monotone, so the lower clamp
 // never acts, and since t, z and qmax are small integers the upper clamp can be
@@ -351,7 +351,9 @@ __device__ __forceinline__ void pack_lane(const float (&v)[EPL], float inv, floa
                                           u32 (&word)[EPL * BITS / 32])
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
-    const bool pack_fast = __builtin_amdgcn_ballot_w64(!(fabsf(zf) <= 2048.0f)) == 0;
+    // strictly below 2048: a zero-point that was rounded to binary16 afterwards (compact metadata) equals the
+    // one Eq. 1 gave only then (2049 rounds to 2048, and the minimum's code then needs the lower clamp)
+    const bool pack_fast = __builtin_amdgcn_ballot_w64(!(fabsf(zf) < 2048.0f)) == 0;
     if (pack_fast) {
         const float tmax = qmax - zf;
         const bool need_cap = __builtin_amdgcn_ballot_w64(rintf(mx * inv) > tmax) != 0;

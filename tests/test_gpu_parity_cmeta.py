@@ -166,6 +166,36 @@ def test_fused_cmeta_arbitrary_codes_and_meta(fc, bits_in):
     assert_pair(gpu_fused_cmeta(fc, c, m, h, group, bits_in, 4), want, "fast path")
 
 
+@pytest.mark.parametrize("bits_out", [4, 8])
+def test_fused_cmeta_zero_point_rounded_to_2048(fc, bits_out):
+    # Sums whose Eq. 1 zero-point is +-2049 (stored as +-2048) or sits just around it: the minimum's code is then
+    # rint(min/s) + 2048 = -1 and must be clamped, next to neighbours packed in the same word.  Two INT8 sources
+    # with a power-of-two scale produce such sums exactly: the first spans the code range under a zero-point of
+    # +-2040, the second is a constant that shifts the sum by a few steps.
+    qmax = (1 << bits_out) - 1
+    s_in = 0.25 if bits_out == 4 else 2.0 ** -6
+    h, group = 4096, 128
+    rng = np.random.default_rng(44)
+    targets = (2049, 2048, 2047, 2050, 2051, -2049, -2048, -2050)
+    c = np.zeros((2, len(targets), h), np.uint8)
+    m = np.zeros((2, len(targets), h // group), np.uint32)
+    half = lambda v: int(np.float16(v).view(np.uint16))
+    for r, z_target in enumerate(targets):
+        z1 = 2040 if z_target > 0 else -2040
+        q = rng.integers(0, qmax + 1, size=h).astype(np.uint8)
+        q[0::group] = 0                        # every group holds its minimum ...
+        q[1::group] = 0                        # ... twice in one packed word ...
+        q[5::group] = qmax                     # ... and its maximum
+        c[0, r] = q
+        m[0, r] = half(s_in) | (half(z1) << 16)
+        m[1, r] = half(s_in) | (half(z_target - z1) << 16)      # codes 0: contributes -(z_target - z1) steps
+    want = oracle.dequant_reduce_requant_cmeta(c, m, h, group, 8, bits_out)
+    s_out, z_out = oracle.meta_unpack(want[1])
+    assert (s_out == np.float32(s_in)).all()
+    assert [float(v) for v in z_out[:, 0]] == [2048.0, 2048.0, 2047.0, 2050.0, 2052.0, -2048.0, -2048.0, -2050.0]
+    assert_pair(gpu_fused_cmeta(fc, c, m, h, group, 8, bits_out), want, "zero-point around 2048, %d bit" % bits_out)
+
+
 @pytest.mark.parametrize("kind", range(synth_inputs.STRESS_KINDS))
 def test_fused_cmeta_value_distributions(fc, kind):
     rng = np.random.default_rng(60 + kind)

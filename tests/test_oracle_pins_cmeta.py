@@ -33,7 +33,7 @@ def load_golden_cmeta(golden_dir):
                                   acc=np.array(f[4].split(), dtype=np.float32), meta=int(f[5], 16),
                                   codes=np.array(f[6].split(), dtype=np.uint8), xhat=from_bits(f[7].split()),
                                   half=np.array([int(w, 16) for w in f[8].split()], dtype=np.uint16))
-    assert len(groups) == 12 and len(reds) == 2
+    assert len(groups) == 13 and len(reds) == 2
     return groups, reds
 
 
