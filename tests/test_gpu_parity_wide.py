@@ -233,6 +233,58 @@ def test_large_volume_offsets_beyond_32_bits(fc):
     assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), "large volume output"
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_randomized_sweep_of_every_quantizer_end_to_end(fc, seed):
+    # 250 random (shape, group, fan-in, bit-width, value distribution) draws per seed; every quantizer's
+    # fc_allreduce_sim* and the compact-metadata stages against the oracle.  (A sweep of this kind found the
+    # zero-point-2049 case of the compact-metadata packer.)
+    rng = np.random.default_rng(seed)
+
+    def draw(n, t, h):
+        kind = int(rng.integers(0, 6))
+        if kind == 0:
+            x = rng.standard_normal((n, t, h))
+        elif kind == 1:
+            x = rng.standard_normal((n, t, h)) * np.exp(rng.uniform(-12, 10, (n, t, 1)))
+        elif kind == 2:
+            x = rng.uniform(100, 101, (n, t, h)) * rng.choice([-1, 1])
+        elif kind == 3:
+            x = np.round(rng.standard_normal((n, t, h)) * 4) / 2
+        elif kind == 4:
+            x = rng.standard_normal((n, t, h)) * (rng.random((n, t, h)) < 0.02) * 1000
+        else:
+            x = rng.standard_normal((n, t, h)) * 1e-6 + rng.choice([0, 3, -500, 60000])
+        return np.clip(x, -65504, 65504).astype(np.float16)
+
+    def same16(got, want, what):
+        assert same_bits(got.cpu().numpy().view(np.uint16), want.view(np.uint16)), what
+
+    for case in range(250):
+        group = int(rng.choice([32, 64, 128, 256, 512, 1024, 2048, 4096, 8192]))
+        hidden = group * int(rng.integers(1, max(2, 8192 // group) + 1))
+        tokens, n = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        bi, bo = int(rng.choice([4, 8])), int(rng.choice([4, 8]))
+        x = draw(n, tokens, hidden)
+        xd = dev(x.view(np.uint16)).view(torch.float16)
+        what = "seed %d case %d: N=%d %dx%d g=%d %d->%d" % (seed, case, n, tokens, hidden, group, bi, bo)
+        same16(fc.allreduce_sim(xd, group, bi, bo), oracle.allreduce_sim(x, group, bi, bo), what + " asym")
+        same16(fc.allreduce_sim_sym(xd, group, bi, bo), oracle.allreduce_sim_sym(x, group, bi, bo), what + " sym")
+        same16(fc.allreduce_sim_fp8(xd, group), oracle.allreduce_sim_fp8(x, group), what + " fp8")
+        same16(fc.allreduce_sim_cmeta(xd, group, bi, bo), oracle.allreduce_sim_cmeta(x, group, bi, bo), what + " cmeta")
+        pm = [oracle.quantize_cmeta(x[j], group, bi) for j in range(n)]
+        cm = np.stack([p[0] for p in pm]); mm = np.stack([p[1] for p in pm])
+        gq = fc.quantize_cmeta(xd[0], group, bi)
+        assert same_bits(gq[0].cpu().numpy(), pm[0][0]) and same_bits(gq[1].cpu().numpy().view(np.uint32), pm[0][1]), what
+        gf = fc.dequant_reduce_requant_cmeta(dev(cm), dev(mm.view(np.int32)), hidden, group, bi, bo)
+        wf = oracle.dequant_reduce_requant_cmeta(cm, mm, hidden, group, bi, bo)
+        assert same_bits(gf[0].cpu().numpy(), wf[0]) and same_bits(gf[1].cpu().numpy().view(np.uint32), wf[1]), what
+        if hidden in (2048, 4096, 8192):
+            q = int(rng.integers(0, 3))
+            b8 = (8, 8) if q == 2 else (bi, bo)
+            same16(fc.allreduce_sim_rot(xd, group, b8[0], b8[1], q), oracle.allreduce_sim_rot(x, group, b8[0], b8[1], q),
+                   what + " rot %d" % q)
+
+
 @pytest.mark.parametrize("variant", ["sym", "fp8", "cmeta"])
 def test_large_volume_other_quantizers(fc, variant):
     # 2^32 + 24576 elements through the symmetric, FP8 and compact-metadata kernels at 8 bit: element
