@@ -198,6 +198,29 @@ def test_fused_arbitrary_scales_and_zero_points(fc, bits_in):
                        "arbitrary meta %d->%d" % (bits_in, bits_out))
 
 
+@pytest.mark.parametrize("bits_in", [4, 8])
+def test_fused_extreme_scales(fc, bits_in):
+    # source scales from the smallest subnormal to 1e35: sums that are subnormal or vanish (the constant-group
+    # rule of Eq. 1 on tiny ranges), and output scales beyond 2^100 (the reciprocal's slow branch)
+    rng = np.random.default_rng(15)
+    n_src, t, h, group = 2, 9, 2048, 128
+    ladder = np.array([1.4e-45, 1e-42, 1e-40, 1.1754944e-38, 1.2e-38, 1e-30, 1.0, 1e30, 2.0 ** 100, 2.0 ** 101, 1e35],
+                      np.float32)
+    c = rng.integers(0, 256, size=(n_src, t, h * bits_in // 8), dtype=np.uint8)
+    s = ladder[rng.integers(0, ladder.size, size=(n_src, t, h // group))]
+    s[:, 0] = ladder[0]; s[:, 1] = ladder[3]; s[:, 2] = ladder[8]; s[:, 3] = ladder[10]     # uniform rows too
+    s[0, 4] = ladder[9]; s[1, 4] = ladder[1]
+    z = np.rint(rng.uniform(-20, 300, size=s.shape)).astype(np.float32)
+    for bits_out in (4, 8):
+        want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+        assert np.isfinite(want[1]).all() and (want[1] > 2.0 ** 100).any() and (want[1] < 1e-37).any()
+        assert_triplet(gpu_fused(fc, c, s, z, h, group, bits_in, bits_out), want,
+                       "extreme scales %d->%d" % (bits_in, bits_out))
+        y = oracle.dequantize(*want, h, group, bits_out)
+        got = gpu_dequantize(fc, *want, h, group, bits_out)
+        assert same_bits(got.view(np.uint16), y.view(np.uint16)), "extreme scales, dequantize"
+
+
 def test_fused_adversarial_sums(fc):
     # sums that are constant, zero, or nearly constant on a large offset
     group = 128

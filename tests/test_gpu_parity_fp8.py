@@ -114,6 +114,20 @@ def test_fused_fp8_arbitrary_codes_and_scales(fc):
         assert_pair(gpu_fused_fp8(fc, c, s, h, group), want, "arbitrary codes N=%d g=%d" % (n_src, group))
 
 
+def test_fused_fp8_extreme_scales(fc):
+    from test_gpu_parity_sym import extreme_scales
+    rng = np.random.default_rng(26)
+    n_src, t, h, group = 2, 9, 2048, 128
+    c = finite_codes(rng, (n_src, t, h))
+    s = extreme_scales(rng, (n_src, t, h // group))
+    want = oracle.dequant_reduce_requant_fp8(c, s, h, group)
+    assert np.isfinite(want[1]).all() and (want[1] > 2.0 ** 100).any() and (want[1] == 1.0).any()
+    assert_pair(gpu_fused_fp8(fc, c, s, h, group), want, "extreme scales")
+    y = oracle.dequantize_fp8(*want, h, group)
+    got = gpu_dequantize_fp8(fc, *want, h, group)
+    assert same_bits(got.view(np.uint16), y.view(np.uint16)), "extreme scales, dequantize_fp8"
+
+
 def test_fused_fp8_wide_groups_and_padding(fc):
     for (t, h, g) in WIDE:
         for n_src in (1, 4, 8):

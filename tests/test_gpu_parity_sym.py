@@ -117,6 +117,34 @@ def test_fused_sym_arbitrary_codes_and_scales(fc, bits_in):
                     "arbitrary codes %d->%d" % (bits_in, bits_out))
 
 
+LADDER = np.array([1.4e-45, 1e-42, 1e-40, 1.1754944e-38, 1.2e-38, 1e-30, 1.0, 1e30, 2.0 ** 100, 2.0 ** 101, 1e35],
+                  np.float32)
+
+
+def extreme_scales(rng, shape):
+    """per-group scales from the smallest subnormal to 1e35, with some rows uniform"""
+    s = LADDER[rng.integers(0, LADDER.size, size=shape)]
+    s[:, 0] = LADDER[0]; s[:, 1] = LADDER[3]; s[:, 2] = LADDER[8]; s[:, 3] = LADDER[10]
+    s[0, 4] = LADDER[9]; s[-1, 4] = LADDER[1]
+    return s
+
+
+@pytest.mark.parametrize("bits_in", [4, 8])
+def test_fused_sym_extreme_scales(fc, bits_in):
+    # sums that are subnormal or vanish (scale 1) and output scales beyond 2^100 (the reciprocal's slow branch)
+    rng = np.random.default_rng(25)
+    n_src, t, h, group = 2, 9, 2048, 128
+    c = rng.integers(0, 256, size=(n_src, t, h * bits_in // 8), dtype=np.uint8)
+    s = extreme_scales(rng, (n_src, t, h // group))
+    for bits_out in (4, 8):
+        want = oracle.dequant_reduce_requant_sym(c, s, h, group, bits_in, bits_out)
+        assert np.isfinite(want[1]).all() and (want[1] > 2.0 ** 100).any() and (want[1] == 1.0).any()
+        assert_pair(gpu_fused_sym(fc, c, s, h, group, bits_in, bits_out), want, "extreme scales %d->%d" % (bits_in, bits_out))
+        y = oracle.dequantize_sym(*want, h, group, bits_out)
+        got = gpu_dequantize_sym(fc, *want, h, group, bits_out)
+        assert same_bits(got.view(np.uint16), y.view(np.uint16)), "extreme scales, dequantize_sym"
+
+
 def test_fused_sym_cancelling_sums(fc):
     # x + (-x): the codes are exact negatives, so what the fused multiply-adds leave is the rounding
     # error of the first product q*s (or an exact zero): sums some 2^-24 below the inputs
