@@ -407,7 +407,8 @@ def test_full_size_configs_on_sampled_rows(fc, name):
     assert bool((zo == torch.round(zo)).all())
 
 
-def test_entry_points_capture_into_a_hip_graph_and_replay(fc):
+@pytest.mark.parametrize("variant", ["asym", "sym", "fp8", "cmeta", "rot"])
+def test_entry_points_capture_into_a_hip_graph_and_replay(fc, variant):
     # the library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so a
     # whole all-reduce captures into a HIP graph; every replay, with eager work in between, must
     # reproduce the eager result
@@ -417,13 +418,25 @@ def test_entry_points_capture_into_a_hip_graph_and_replay(fc):
     y = torch.empty((w.tokens, w.hidden), dtype=torch.float16, device="cuda")
     ws = torch.empty(fc.allreduce_sim_workspace_bytes(w.n_src, w.tokens, w.hidden, w.group, w.bits_in, w.bits_out),
                      dtype=torch.uint8, device="cuda")
-    want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
-    fc.allreduce_sim(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws)      # eager, loads the kernels
+    gpu_sim, cpu_sim = {
+        "asym": (lambda: fc.allreduce_sim(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws),
+                 lambda a: oracle.allreduce_sim(a, w.group, w.bits_in, w.bits_out)),
+        "sym": (lambda: fc.allreduce_sim_sym(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws),
+                lambda a: oracle.allreduce_sim_sym(a, w.group, w.bits_in, w.bits_out)),
+        "fp8": (lambda: fc.allreduce_sim_fp8(xd, w.group, out=y, workspace=ws),
+                lambda a: oracle.allreduce_sim_fp8(a, w.group)),
+        "cmeta": (lambda: fc.allreduce_sim_cmeta(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws),
+                  lambda a: oracle.allreduce_sim_cmeta(a, w.group, w.bits_in, w.bits_out)),
+        "rot": (lambda: fc.allreduce_sim_rot(xd, w.group, w.bits_in, w.bits_out, fc.QUANTIZER_ASYM, out=y, workspace=ws),
+                lambda a: oracle.allreduce_sim_rot(a, w.group, w.bits_in, w.bits_out, oracle.ASYM)),
+    }[variant]
+    want = cpu_sim(x)
+    gpu_sim()                                                                       # eager, loads the kernels
     torch.cuda.synchronize()
     assert same_bits(y.cpu().numpy().view(np.uint16), want.view(np.uint16))
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=torch.cuda.Stream()):
-        fc.allreduce_sim(xd, w.group, w.bits_in, w.bits_out, out=y, workspace=ws)
+        gpu_sim()
     for rep in range(4):
         y.fill_(7.0); ws.fill_(0x5A)
         torch.cuda.synchronize()
@@ -435,7 +448,7 @@ def test_entry_points_capture_into_a_hip_graph_and_replay(fc):
         # new input for the next replay: the graph reads the buffers, not captured values
         x = synth_inputs.make_partials(w.n_src, w.tokens, w.hidden, seed=100 + rep)
         xd.copy_(dev(x.view(np.uint16)).view(torch.float16))
-        want = oracle.allreduce_sim(x, w.group, w.bits_in, w.bits_out)
+        want = cpu_sim(x)
 
 
 @pytest.mark.parametrize("n_src", [1, 3, 8])
