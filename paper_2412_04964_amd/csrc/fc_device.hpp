@@ -54,6 +54,10 @@ constexpr int block_elems(int bits) { return kBlockThreads * lane_elems(bits); }
 // copy, up to 3 % on the 8-bit fused kernel).  The run-time-LPG instantiation keeps 256 threads,
 // the span over which it can reduce a group across wavefronts.
 constexpr int fused_block_threads(int lpg) { return lpg > 0 ? 128 : kBlockThreads; }
+// Launch-bound volumes (at most one wavefront per compute unit of the part): the asymmetric g = 128 instantiations
+// also exist with single-wavefront workgroups, which spreads the work over twice as many compute units and turns the
+// wavefront index into a constant (decode shape: 3.46 -> 3.30 us per launch).
+constexpr int kSmallLaunchWaves = 256;
 // The stand-alone 4-bit quantizer gains the same way (1.8 %); the 8-bit one and the dequantizer do not.
 constexpr int quantize_block_threads(int bits, int lpg) { return (bits == 4 && lpg > 0) ? 128 : kBlockThreads; }
 
@@ -899,8 +903,10 @@ __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
 // compile time by the group width (see kDirectMeta below).
 // HM = true: binary16 metadata; scales_in / scales_out are the arrays of 32-bit
 // metadata words and the zeros arrays are not used.
-template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool HM = false>
-__global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_requant(
+// BT: threads per workgroup.  Besides the default, the launcher uses single-wavefront workgroups (BT = 64, narrow
+// groups only) for volumes too small to give every compute unit a wavefront.
+template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool HM = false, int BT = fused_block_threads(LPG)>
+__global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, const float *__restrict__ zeros_in, int64_t meta_stride,
     int64_t n_elems, int lpg, int group_shift,
@@ -908,7 +914,8 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 {
     constexpr int EPL = lane_elems(BITS_IN);
     constexpr int kWaveElems = 64 * EPL;
-    constexpr int BT = fused_block_threads(LPG), kWaves = BT / 64;
+    constexpr int kWaves = BT / 64;
+    static_assert(BT == fused_block_threads(LPG) || (BT == 64 && LPG > 0), "unsupported workgroup size");
     constexpr int kTileElems = BT * EPL;
     constexpr int kOutBytes = EPL * BITS_OUT / 8;             // code bytes a lane writes: 8, 16 or 32
     constexpr int kMaxGw = LPG > 0 ? 64 / LPG : 8;            // groups per wavefront tile (upper bound)

@@ -46,6 +46,18 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
+    if constexpr (LPG == 128 / lane_elems(FC_BITS_IN)) {     // g = 128: small volumes in single-wavefront workgroups
+        const int64_t wave_elems = 64 * lane_elems(FC_BITS_IN);
+        const int64_t waves = (a.n_elems + wave_elems - 1) / wave_elems;
+        if (waves <= kSmallLaunchWaves) {
+            k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, false, 64>
+                <<<dim3((unsigned)waves), dim3(64), 0, stream>>>(
+                    static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
+                    a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                    static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
+            return hipGetLastError();
+        }
+    }
     k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
         <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
