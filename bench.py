@@ -80,6 +80,7 @@ def cpu_baseline(w, x_host, budget_s=20.0):
         rows = max(16, int(w.tokens * budget_s / (est * 3)))
     xs = x_host[:, :rows]
     sym, fp8, cm = w.quantizer == "sym", w.quantizer == "fp8", w.quantizer == "cmeta"
+    t_q = time.perf_counter()
     if fp8:
         parts = [oracle.quantize_fp8(xs[j], w.group) for j in range(w.n_src)]
     elif cm:
@@ -87,21 +88,32 @@ def cpu_baseline(w, x_host, budget_s=20.0):
     else:
         parts = [(oracle.quantize_sym if sym else oracle.quantize)(xs[j], w.group, w.bits_in)
                  for j in range(w.n_src)]
+    t_q = time.perf_counter() - t_q                       # the first stage: n_src quantizations, timed once
     c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
     z = None if (sym or fp8 or cm) else np.stack([p[2] for p in parts])
     best = None
     for _ in range(2):
         t0 = time.perf_counter()
         if fp8:
-            oracle.dequant_reduce_requant_fp8(c, s, w.hidden, w.group)
+            fused = oracle.dequant_reduce_requant_fp8(c, s, w.hidden, w.group)
         elif sym:
-            oracle.dequant_reduce_requant_sym(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
+            fused = oracle.dequant_reduce_requant_sym(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
         elif cm:
-            oracle.dequant_reduce_requant_cmeta(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
+            fused = oracle.dequant_reduce_requant_cmeta(c, s, w.hidden, w.group, w.bits_in, w.bits_out)
         else:
-            oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
+            fused = oracle.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
+    t_d = time.perf_counter()                             # the last stage, timed once
+    if fp8:
+        oracle.dequantize_fp8(*fused, w.hidden, w.group)
+    elif sym:
+        oracle.dequantize_sym(*fused, w.hidden, w.group, w.bits_out)
+    elif cm:
+        oracle.dequantize_cmeta(*fused, w.hidden, w.group, w.bits_out)
+    else:
+        oracle.dequantize(*fused, w.hidden, w.group, w.bits_out)
+    t_d = time.perf_counter() - t_d
     frac = rows / w.tokens
     return {
         "value": round(fused_bytes(w) * frac / best / 1e9, 4),
@@ -111,6 +123,8 @@ def cpu_baseline(w, x_host, budget_s=20.0):
         "sample": "fused step of the plain-C oracle on rows [0,%d) of %d of volume 0, best of 2, "
                   "%.2f s per run" % (rows, w.tokens, best),
         "host_cpus": os.cpu_count(),
+        "other_stages_GBps": {"quantize_xN": round(w.n_src * quantize_bytes(w) * frac / t_q / 1e9, 4),
+                              "dequantize": round(dequantize_bytes(w) * frac / t_d / 1e9, 4)},
     }
 
 
