@@ -137,6 +137,26 @@ FC_API size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_
                                                int bits_rs, int bits_ag);
 
 /*
+ * fc_allreduce_sim for callers that cannot allocate device memory or keep a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the same
+ * kernels, with the intermediate codes, scales and zero-points in a fixed array of
+ * FC_STATIC_SCRATCH_BYTES that lives in the library's device image (one copy per GPU, held until
+ * the process ends).  The call allocates and frees nothing.  Same arguments, results and errors
+ * as fc_allreduce_sim, plus:
+ *   - FC_ERR_WORKSPACE when fc_allreduce_sim_workspace_bytes(...) exceeds
+ *     FC_STATIC_SCRATCH_BYTES (e.g. 8 partials of 128 x 8192 at 8 bit, group 128, need 9.6 MB;
+ *     the prefill volumes do not fit and must use fc_allreduce_sim);
+ *   - all calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ *     (different streams, different threads) race; serialize them;
+ *   - the first call on a device looks up the array's address (hipGetSymbolAddress); make
+ *     that call outside graph capture.
+ */
+#define FC_STATIC_SCRATCH_BYTES (32u << 20)
+
+FC_API int fc_allreduce_sim_static(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                                   int group, int bits_rs, int bits_ag, void *y_f16, void *hip_stream);
+
+/*
  * Symmetric variant (Appendix "Quantization Fundamentals", Eq. 3-4; the paper's
  * INT8_Sym / INT4_Sym ablation rows).  Same layouts and rules as above except:
  * there is no zero-point array, and codes are SIGNED, stored in two's

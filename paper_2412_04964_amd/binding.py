@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize.restype = i32
         L.fc_allreduce_sim.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim.restype = i32
+        L.fc_allreduce_sim_static.argtypes = [vp, i32, i64, i64, i32, i32, i32, vp, vp]
+        L.fc_allreduce_sim_static.restype = i32
         L.fc_allreduce_sim_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i32]
         L.fc_allreduce_sim_workspace_bytes.restype = sz
         L.fc_quantize_sym.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
@@ -219,6 +221,22 @@ def allreduce_sim(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace
     _check(lib().fc_allreduce_sim(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream()),
            "fc_allreduce_sim")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20      # FC_STATIC_SCRATCH_BYTES of include/fc.h
+
+
+def allreduce_sim_static(x, group: int, bits_rs: int, bits_ag: int, out=None):
+    """fc_allreduce_sim_static: fc_allreduce_sim with the intermediates in the library's own fixed
+    scratch array.  The C call allocates nothing; pass `out` to keep this wrapper from allocating too."""
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    n, t, h = x.shape
+    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    _check(lib().fc_allreduce_sim_static(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
+                                         _stream()), "fc_allreduce_sim_static")
     return y
 
 

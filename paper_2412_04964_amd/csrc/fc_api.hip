@@ -5,11 +5,22 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "fc_launch.hpp"
+
+// Scratch of fc_allreduce_sim_static: the intermediate codes, scales and zero-points of one
+// all-reduce.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress; the device
+// address it returns is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[FC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];     // device address of `scratch`, per device
 
 constexpr int64_t kMaxElems = (int64_t)1 << 36;   // keeps grid*block below 2^32 threads
 
@@ -195,6 +206,24 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
                            bits_ag, y_f16, hip_stream);
 }
 
+// Device address of the current device's copy of `scratch`, looked up once per device.
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_result(e);
+    if (dev < 0 || dev >= kMaxDevices) return hip_result(hipErrorInvalidDevice);
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_result(e);
+        if (!p) return hip_result(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread finds the same address
+    }
+    *ptr = p;
+    return FC_OK;
+}
+
 bool rot_hidden_ok(int64_t hidden) { return hidden == 2048 || hidden == 4096 || hidden == 8192; }
 
 int check_quantizer(int quantizer, int bits)
@@ -308,6 +337,28 @@ int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidde
 {
     return allreduce_sim_impl(fc::CODEC_ASYM, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
                               workspace, workspace_bytes, hip_stream);
+}
+
+int fc_allreduce_sim_static(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
+                            int group, int bits_rs, int bits_ag, void *y_f16, void *hip_stream)
+{
+    int64_t n = 0;
+    const int rc = check_shape(tokens, hidden, group, bits_rs, &n);
+    if (rc != FC_OK) return rc;
+    if (bits_ag != 4 && bits_ag != 8) return FC_ERR_BITS;
+    if (n_src < 1 || n_src > FC_MAX_SRC) return FC_ERR_SHAPE;
+    if (n == 0) return FC_OK;
+    if (!x_f16 || !y_f16) return FC_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return FC_ERR_ALIGN;
+    if (sim_layout(n_src, n, group, bits_rs, bits_ag).total > (size_t)FC_STATIC_SCRATCH_BYTES)
+        return FC_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int sc = static_scratch(&ws);
+    if (sc != FC_OK) return sc;
+    // nothing in the scratch has to start at zero: every byte a kernel reads there was written by
+    // the kernel before it in this call
+    return allreduce_sim_impl(fc::CODEC_ASYM, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
+                              ws, (size_t)FC_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
@@ -462,7 +513,7 @@ const char *fc_strerror(int code)
     case FC_ERR_GROUP: return "group must be a power of two in [32, 16384] that divides hidden";
     case FC_ERR_SHAPE: return "bad tokens / hidden / n_src / source stride";
     case FC_ERR_ALIGN: return "pointers and strides must be 16-byte aligned";
-    case FC_ERR_WORKSPACE: return "workspace missing or too small";
+    case FC_ERR_WORKSPACE: return "workspace missing or too small (or volume beyond the static scratch)";
     case FC_ERR_HIP: return "HIP launch failed (see fc_last_hip_error)";
     default: return "unknown error code";
     }
