@@ -45,6 +45,10 @@
  *   - Inputs must be finite.  NaN / Inf inputs give unspecified codes.
  *   - Return value: FC_OK or a negative FC_ERR_* code.  Argument checks come
  *     first and make no HIP call, so they work on a host without a GPU.
+ *     FC_ERR_HIP reports the status that the launch call itself returned (kept for
+ *     fc_last_hip_error); the library never reads or clears the calling thread's
+ *     HIP last-error state, so an error left there by other code is neither
+ *     reported as ours nor consumed.
  */
 #ifndef FC_H
 #define FC_H
@@ -281,17 +285,6 @@ FC_API int fc_dequantize_rot(const void *codes, const float *scales, const float
 FC_API int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
                                 int group, int bits_rs, int bits_ag, int quantizer, void *y_f16,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
-
-/*
- * Measurement aid, not part of the paper's method: the memory access pattern of
- * fc_dequant_reduce_requant with the arithmetic taken out.  Reads n_src device arrays of `bytes`
- * bytes (source j at in + j*in_src_stride_bytes) and writes their bytewise XOR to `out` (`bytes`
- * bytes), with the fused kernel's tiling, staging and cache policy.  bytes % 16 == 0; pointers and
- * stride 16-byte aligned.  bench.py times it next to the fused kernel to show how much of the
- * bandwidth this access pattern can reach on the machine at hand.
- */
-FC_API int fc_stream_reference(const void *in, int64_t in_src_stride_bytes, int n_src, int64_t bytes,
-                               void *out, void *hip_stream);
 
 /* Static, NUL-terminated description of an FC_* code.  Host pointer, never NULL. */
 FC_API const char *fc_strerror(int code);

@@ -11,7 +11,9 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # FC_LIBRARY overrides the location of the shared library (e.g. a differently tuned build)
 _LIB_PATH = os.environ.get("FC_LIBRARY") or os.path.join(_HERE, "libfc.so")
+_BENCH_LIB_PATH = os.environ.get("FC_BENCH_LIBRARY") or os.path.join(_HERE, "libfc_bench.so")
 _lib = None
+_bench_lib = None
 
 FC_MAX_SRC = 8
 QUANTIZER_ASYM, QUANTIZER_SYM, QUANTIZER_FP8 = 0, 1, 2
@@ -85,8 +87,6 @@ def lib() -> ctypes.CDLL:
         L.fc_dequantize_rot.restype = i32
         L.fc_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
         L.fc_allreduce_sim_rot.restype = i32
-        L.fc_stream_reference.argtypes = [vp, i64, i32, i64, vp, vp]
-        L.fc_stream_reference.restype = i32
         L.fc_strerror.argtypes = [i32]
         L.fc_strerror.restype = ctypes.c_char_p
         L.fc_last_hip_error.argtypes = []
@@ -126,6 +126,41 @@ def _dev(t, dtype, what):
         raise TypeError("%s must be %s, got %s" % (what, dtype, t.dtype))
     if not t.is_contiguous():
         raise ValueError("%s must be contiguous" % what)
+    if t.device.index != torch.cuda.current_device():
+        raise ValueError("%s lives on %s but the current device is cuda:%d; the C ABI works on the current device"
+                         % (what, t.device, torch.cuda.current_device()))
+    return t
+
+
+# The kernels take every buffer range from (tokens, hidden, group, bits), never from the allocation, so a tensor
+# whose shape disagrees with those numbers would be read or written out of bounds: each wrapper compares every
+# tensor's shape with the geometry before the C call.
+
+def _geometry(what: str, hidden: int, group: int, *bits: int):
+    """The C library's own argument errors, raised before any shape arithmetic that would divide by them."""
+    for b in bits:
+        if b not in (4, 8):
+            raise FcError(-2, what)
+    if group < 32 or group > 16384 or (group & (group - 1)):
+        raise FcError(-3, what)
+    if hidden <= 0:
+        raise FcError(-4, what)
+    if hidden % group:
+        raise FcError(-3, what)
+
+
+def _shape(t, want, what: str):
+    if tuple(t.shape) != tuple(want):
+        raise ValueError("%s must have shape %s for these arguments, got %s" % (what, tuple(want), tuple(t.shape)))
+    return t
+
+
+def _sources(t, what: str):
+    """[N, tokens, bytes-or-groups] stacked on the source axis, each source's slab dense"""
+    if t.dim() != 3:
+        raise ValueError("%s must be [n_src, tokens, ...], got shape %s" % (what, tuple(t.shape)))
+    if not 1 <= t.shape[0] <= FC_MAX_SRC:
+        raise FcError(-4, what)
     return t
 
 
@@ -134,22 +169,82 @@ def _check(rc: int, what: str):
         raise FcError(rc, what)
 
 
+def _x2(x, what="x"):
+    torch = _torch()
+    _dev(x, torch.float16, what)
+    if x.dim() != 2:
+        raise ValueError("%s must be float16 [tokens, hidden], got shape %s" % (what, tuple(x.shape)))
+    return x.shape
+
+
+def _x3(x):
+    torch = _torch()
+    _dev(x, torch.float16, "x")
+    _sources(x, "x")
+    return x.shape
+
+
+def _coded_outputs(device, t, h, group, bits, out, meta):
+    """codes u8 [t, h*bits/8] plus one [t, h/group] array per entry of `meta` (its dtype, its name): allocated
+    here, or the caller's `out` tuple checked against those shapes."""
+    torch = _torch()
+    if out is None:
+        return (torch.empty((t, h * bits // 8), dtype=torch.uint8, device=device),
+                *[torch.empty((t, h // group), dtype=dt, device=device) for dt, _ in meta])
+    if len(out) != 1 + len(meta):
+        raise ValueError("out must hold %d tensors" % (1 + len(meta)))
+    _shape(_dev(out[0], torch.uint8, "codes (out)"), (t, h * bits // 8), "codes (out)")
+    for o, (dt, name) in zip(out[1:], meta):
+        _shape(_dev(o, dt, name + " (out)"), (t, h // group), name + " (out)")
+    return tuple(out)
+
+
+def _coded_inputs(codes, metas, hidden, group, bits, meta):
+    """codes u8 [t, hidden*bits/8] and the [t, hidden/group] metadata arrays of one quantized tensor"""
+    torch = _torch()
+    _dev(codes, torch.uint8, "codes")
+    if codes.dim() != 2:
+        raise ValueError("codes must be [tokens, hidden*bits/8], got shape %s" % (tuple(codes.shape),))
+    t = codes.shape[0]
+    _shape(codes, (t, hidden * bits // 8), "codes")
+    for m, (dt, name) in zip(metas, meta):
+        _shape(_dev(m, dt, name), (t, hidden // group), name)
+    return t
+
+
+def _stacked_inputs(codes_in, metas, hidden, group, bits_in, meta):
+    """codes_in u8 [N, t, hidden*bits_in/8] and metadata [N, t, hidden/group]; returns (N, t, code stride in
+    bytes, metadata stride in elements) of the dense slabs"""
+    torch = _torch()
+    _sources(_dev(codes_in, torch.uint8, "codes_in"), "codes_in")
+    n, t = codes_in.shape[0], codes_in.shape[1]
+    _shape(codes_in, (n, t, hidden * bits_in // 8), "codes_in")
+    for m, (dt, name) in zip(metas, meta):
+        _shape(_dev(m, dt, name), (n, t, hidden // group), name)
+    return n, t, (codes_in.stride(0) if n > 1 else 0), (metas[0].stride(0) if n > 1 else 0)
+
+
+def _y_out(device, t, h, out):
+    torch = _torch()
+    if out is None:
+        return torch.empty((t, h), dtype=torch.float16, device=device)
+    return _shape(_dev(out, torch.float16, "y (out)"), (t, h), "y (out)")
+
+
+def _f32(name):
+    return (_torch().float32, name)
+
+
+def _i32(name):
+    return (_torch().int32, name)
+
+
 def quantize(x, group: int, bits: int, out=None):
     """fc_quantize.  x: float16 [tokens, hidden] -> (codes u8 [tokens, hidden*bits/8],
     scales f32 [tokens, hidden/group], zeros f32 [tokens, hidden/group])."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    t, h = x.shape
-    if out is None:
-        if bits not in (4, 8) or group <= 0 or h % group:
-            _check(lib().fc_quantize(None, t, h, group, bits, None, None, None, None), "fc_quantize")
-        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
-        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
-        zeros = torch.empty_like(scales)
-    else:
-        codes, scales, zeros = out
-        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
-        _dev(zeros, torch.float32, "zeros")
+    t, h = _x2(x)
+    _geometry("fc_quantize", h, group, bits)
+    codes, scales, zeros = _coded_outputs(x.device, t, h, group, bits, out, [_f32("scales"), _f32("zeros")])
     _check(lib().fc_quantize(x.data_ptr(), t, h, group, bits, codes.data_ptr(), scales.data_ptr(),
                              zeros.data_ptr(), _stream()), "fc_quantize")
     return codes, scales, zeros
@@ -159,26 +254,11 @@ def dequant_reduce_requant(codes_in, scales_in, zeros_in, hidden: int, group: in
                            bits_in: int, bits_out: int, out=None):
     """fc_dequant_reduce_requant.  Inputs stacked on a leading source axis:
     codes_in u8 [N, tokens, hidden*bits_in/8], scales_in / zeros_in f32 [N, tokens, hidden/group]."""
-    torch = _torch()
-    _dev(codes_in, torch.uint8, "codes_in"); _dev(scales_in, torch.float32, "scales_in")
-    _dev(zeros_in, torch.float32, "zeros_in")
-    n, t = codes_in.shape[0], codes_in.shape[1]
-    if out is None:
-        if bits_out not in (4, 8) or group <= 0 or hidden % group:
-            _check(lib().fc_dequant_reduce_requant(None, 0, None, None, 0, n, t, hidden, group,
-                                                   bits_in, bits_out, None, None, None, None),
-                   "fc_dequant_reduce_requant")
-        codes = torch.empty((t, hidden * bits_out // 8), dtype=torch.uint8, device=codes_in.device)
-        scales = torch.empty((t, hidden // group), dtype=torch.float32, device=codes_in.device)
-        zeros = torch.empty_like(scales)
-    else:
-        codes, scales, zeros = out
-        _dev(codes, torch.uint8, "codes_out"); _dev(scales, torch.float32, "scales_out")
-        _dev(zeros, torch.float32, "zeros_out")
-    cstride = codes_in.stride(0) if n > 1 else 0
-    mstride = scales_in.stride(0) if n > 1 else 0
-    if n > 1 and zeros_in.stride(0) != mstride:
-        raise ValueError("scales_in and zeros_in must share the source stride")
+    _geometry("fc_dequant_reduce_requant", hidden, group, bits_in, bits_out)
+    n, t, cstride, mstride = _stacked_inputs(codes_in, (scales_in, zeros_in), hidden, group, bits_in,
+                                             [_f32("scales_in"), _f32("zeros_in")])
+    codes, scales, zeros = _coded_outputs(codes_in.device, t, hidden, group, bits_out, out,
+                                          [_f32("scales"), _f32("zeros")])
     _check(lib().fc_dequant_reduce_requant(
         codes_in.data_ptr(), cstride, scales_in.data_ptr(), zeros_in.data_ptr(), mstride, n, t,
         hidden, group, bits_in, bits_out, codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
@@ -188,12 +268,9 @@ def dequant_reduce_requant(codes_in, scales_in, zeros_in, hidden: int, group: in
 
 def dequantize(codes, scales, zeros, hidden: int, group: int, bits: int, out=None):
     """fc_dequantize -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
-    _dev(zeros, torch.float32, "zeros")
-    t = codes.shape[0]
-    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
-    _dev(y, torch.float16, "y")
+    _geometry("fc_dequantize", hidden, group, bits)
+    t = _coded_inputs(codes, (scales, zeros), hidden, group, bits, [_f32("scales"), _f32("zeros")])
+    y = _y_out(codes.device, t, hidden, out)
     _check(lib().fc_dequantize(codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), t, hidden,
                                group, bits, y.data_ptr(), _stream()), "fc_dequantize")
     return y
@@ -204,24 +281,27 @@ def allreduce_sim_workspace_bytes(n_src: int, tokens: int, hidden: int, group: i
     return int(lib().fc_allreduce_sim_workspace_bytes(n_src, tokens, hidden, group, bits_rs, bits_ag))
 
 
-def allreduce_sim(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace=None):
-    """fc_allreduce_sim.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
+def _sim(fn_name, x, group, bits_rs, bits_ag, out, workspace, bits_args=True, extra=()):
+    """the fc_allreduce_sim* family: x float16 [N, tokens, hidden] -> float16 [tokens, hidden]"""
     torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
+    n, t, h = _x3(x)
+    _geometry(fn_name, h, group, bits_rs, bits_ag)
     need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
-    if need == 0 and t != 0:
-        _check(lib().fc_allreduce_sim(None, n, t, h, group, bits_rs, bits_ag, None, None, 0, None),
-               "fc_allreduce_sim")
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     _dev(workspace, torch.uint8, "workspace")
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
-    _check(lib().fc_allreduce_sim(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
-                                  workspace.data_ptr(), workspace.numel(), _stream()),
-           "fc_allreduce_sim")
+    if workspace.numel() < need:
+        raise FcError(-6, fn_name)
+    y = _y_out(x.device, t, h, out)
+    bits = (bits_rs, bits_ag) if bits_args else ()
+    _check(getattr(lib(), fn_name)(x.data_ptr(), n, t, h, group, *bits, *extra, y.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), _stream()), fn_name)
     return y
+
+
+def allreduce_sim(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace=None):
+    """fc_allreduce_sim.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
+    return _sim("fc_allreduce_sim", x, group, bits_rs, bits_ag, out, workspace)
 
 
 STATIC_SCRATCH_BYTES = 32 << 20      # FC_STATIC_SCRATCH_BYTES of include/fc.h
@@ -230,11 +310,9 @@ STATIC_SCRATCH_BYTES = 32 << 20      # FC_STATIC_SCRATCH_BYTES of include/fc.h
 def allreduce_sim_static(x, group: int, bits_rs: int, bits_ag: int, out=None):
     """fc_allreduce_sim_static: fc_allreduce_sim with the intermediates in the library's own fixed
     scratch array.  The C call allocates nothing; pass `out` to keep this wrapper from allocating too."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
+    n, t, h = _x3(x)
+    _geometry("fc_allreduce_sim_static", h, group, bits_rs, bits_ag)
+    y = _y_out(x.device, t, h, out)
     _check(lib().fc_allreduce_sim_static(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
                                          _stream()), "fc_allreduce_sim_static")
     return y
@@ -245,17 +323,9 @@ def allreduce_sim_static(x, group: int, bits_rs: int, bits_ag: int, out=None):
 def quantize_sym(x, group: int, bits: int, out=None):
     """fc_quantize_sym.  x: float16 [tokens, hidden] -> (codes u8 [tokens, hidden*bits/8] holding
     signed codes, scales f32 [tokens, hidden/group])."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    t, h = x.shape
-    if out is None:
-        if bits not in (4, 8) or group <= 0 or h % group:
-            _check(lib().fc_quantize_sym(None, t, h, group, bits, None, None, None), "fc_quantize_sym")
-        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
-        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
-    else:
-        codes, scales = out
-        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    t, h = _x2(x)
+    _geometry("fc_quantize_sym", h, group, bits)
+    codes, scales = _coded_outputs(x.device, t, h, group, bits, out, [_f32("scales")])
     _check(lib().fc_quantize_sym(x.data_ptr(), t, h, group, bits, codes.data_ptr(), scales.data_ptr(),
                                  _stream()), "fc_quantize_sym")
     return codes, scales
@@ -265,21 +335,9 @@ def dequant_reduce_requant_sym(codes_in, scales_in, hidden: int, group: int,
                                bits_in: int, bits_out: int, out=None):
     """fc_dequant_reduce_requant_sym.  codes_in u8 [N, tokens, hidden*bits_in/8],
     scales_in f32 [N, tokens, hidden/group]."""
-    torch = _torch()
-    _dev(codes_in, torch.uint8, "codes_in"); _dev(scales_in, torch.float32, "scales_in")
-    n, t = codes_in.shape[0], codes_in.shape[1]
-    if out is None:
-        if bits_out not in (4, 8) or group <= 0 or hidden % group:
-            _check(lib().fc_dequant_reduce_requant_sym(None, 0, None, 0, n, t, hidden, group,
-                                                       bits_in, bits_out, None, None, None),
-                   "fc_dequant_reduce_requant_sym")
-        codes = torch.empty((t, hidden * bits_out // 8), dtype=torch.uint8, device=codes_in.device)
-        scales = torch.empty((t, hidden // group), dtype=torch.float32, device=codes_in.device)
-    else:
-        codes, scales = out
-        _dev(codes, torch.uint8, "codes_out"); _dev(scales, torch.float32, "scales_out")
-    cstride = codes_in.stride(0) if n > 1 else 0
-    mstride = scales_in.stride(0) if n > 1 else 0
+    _geometry("fc_dequant_reduce_requant_sym", hidden, group, bits_in, bits_out)
+    n, t, cstride, mstride = _stacked_inputs(codes_in, (scales_in,), hidden, group, bits_in, [_f32("scales_in")])
+    codes, scales = _coded_outputs(codes_in.device, t, hidden, group, bits_out, out, [_f32("scales")])
     _check(lib().fc_dequant_reduce_requant_sym(
         codes_in.data_ptr(), cstride, scales_in.data_ptr(), mstride, n, t, hidden, group, bits_in,
         bits_out, codes.data_ptr(), scales.data_ptr(), _stream()), "fc_dequant_reduce_requant_sym")
@@ -288,11 +346,9 @@ def dequant_reduce_requant_sym(codes_in, scales_in, hidden: int, group: int,
 
 def dequantize_sym(codes, scales, hidden: int, group: int, bits: int, out=None):
     """fc_dequantize_sym -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
-    t = codes.shape[0]
-    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
-    _dev(y, torch.float16, "y")
+    _geometry("fc_dequantize_sym", hidden, group, bits)
+    t = _coded_inputs(codes, (scales,), hidden, group, bits, [_f32("scales")])
+    y = _y_out(codes.device, t, hidden, out)
     _check(lib().fc_dequantize_sym(codes.data_ptr(), scales.data_ptr(), t, hidden, group, bits,
                                    y.data_ptr(), _stream()), "fc_dequantize_sym")
     return y
@@ -300,22 +356,7 @@ def dequantize_sym(codes, scales, hidden: int, group: int, bits: int, out=None):
 
 def allreduce_sim_sym(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace=None):
     """fc_allreduce_sim_sym.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
-    need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
-    if need == 0 and t != 0:
-        _check(lib().fc_allreduce_sim_sym(None, n, t, h, group, bits_rs, bits_ag, None, None, 0, None),
-               "fc_allreduce_sim_sym")
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
-    _check(lib().fc_allreduce_sim_sym(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
-                                      workspace.data_ptr(), workspace.numel(), _stream()),
-           "fc_allreduce_sim_sym")
-    return y
+    return _sim("fc_allreduce_sim_sym", x, group, bits_rs, bits_ag, out, workspace)
 
 
 # ---- asymmetric quantizer with binary16 metadata: one 32-bit word per group ----
@@ -324,17 +365,9 @@ def allreduce_sim_sym(x, group: int, bits_rs: int, bits_ag: int, out=None, works
 def quantize_cmeta(x, group: int, bits: int, out=None):
     """fc_quantize_cmeta.  x: float16 [tokens, hidden] -> (codes u8 [tokens, hidden*bits/8],
     meta i32 [tokens, hidden/group])."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    t, h = x.shape
-    if out is None:
-        if bits not in (4, 8) or group <= 0 or h % group:
-            _check(lib().fc_quantize_cmeta(None, t, h, group, bits, None, None, None), "fc_quantize_cmeta")
-        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
-        meta = torch.empty((t, h // group), dtype=torch.int32, device=x.device)
-    else:
-        codes, meta = out
-        _dev(codes, torch.uint8, "codes"); _dev(meta, torch.int32, "meta")
+    t, h = _x2(x)
+    _geometry("fc_quantize_cmeta", h, group, bits)
+    codes, meta = _coded_outputs(x.device, t, h, group, bits, out, [_i32("meta")])
     _check(lib().fc_quantize_cmeta(x.data_ptr(), t, h, group, bits, codes.data_ptr(), meta.data_ptr(),
                                    _stream()), "fc_quantize_cmeta")
     return codes, meta
@@ -344,21 +377,9 @@ def dequant_reduce_requant_cmeta(codes_in, meta_in, hidden: int, group: int,
                                  bits_in: int, bits_out: int, out=None):
     """fc_dequant_reduce_requant_cmeta.  codes_in u8 [N, tokens, hidden*bits_in/8],
     meta_in i32 [N, tokens, hidden/group]."""
-    torch = _torch()
-    _dev(codes_in, torch.uint8, "codes_in"); _dev(meta_in, torch.int32, "meta_in")
-    n, t = codes_in.shape[0], codes_in.shape[1]
-    if out is None:
-        if bits_out not in (4, 8) or group <= 0 or hidden % group:
-            _check(lib().fc_dequant_reduce_requant_cmeta(None, 0, None, 0, n, t, hidden, group,
-                                                         bits_in, bits_out, None, None, None),
-                   "fc_dequant_reduce_requant_cmeta")
-        codes = torch.empty((t, hidden * bits_out // 8), dtype=torch.uint8, device=codes_in.device)
-        meta = torch.empty((t, hidden // group), dtype=torch.int32, device=codes_in.device)
-    else:
-        codes, meta = out
-        _dev(codes, torch.uint8, "codes_out"); _dev(meta, torch.int32, "meta_out")
-    cstride = codes_in.stride(0) if n > 1 else 0
-    mstride = meta_in.stride(0) if n > 1 else 0
+    _geometry("fc_dequant_reduce_requant_cmeta", hidden, group, bits_in, bits_out)
+    n, t, cstride, mstride = _stacked_inputs(codes_in, (meta_in,), hidden, group, bits_in, [_i32("meta_in")])
+    codes, meta = _coded_outputs(codes_in.device, t, hidden, group, bits_out, out, [_i32("meta")])
     _check(lib().fc_dequant_reduce_requant_cmeta(
         codes_in.data_ptr(), cstride, meta_in.data_ptr(), mstride, n, t, hidden, group, bits_in,
         bits_out, codes.data_ptr(), meta.data_ptr(), _stream()), "fc_dequant_reduce_requant_cmeta")
@@ -367,11 +388,9 @@ def dequant_reduce_requant_cmeta(codes_in, meta_in, hidden: int, group: int,
 
 def dequantize_cmeta(codes, meta, hidden: int, group: int, bits: int, out=None):
     """fc_dequantize_cmeta -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(codes, torch.uint8, "codes"); _dev(meta, torch.int32, "meta")
-    t = codes.shape[0]
-    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
-    _dev(y, torch.float16, "y")
+    _geometry("fc_dequantize_cmeta", hidden, group, bits)
+    t = _coded_inputs(codes, (meta,), hidden, group, bits, [_i32("meta")])
+    y = _y_out(codes.device, t, hidden, out)
     _check(lib().fc_dequantize_cmeta(codes.data_ptr(), meta.data_ptr(), t, hidden, group, bits,
                                      y.data_ptr(), _stream()), "fc_dequantize_cmeta")
     return y
@@ -379,22 +398,7 @@ def dequantize_cmeta(codes, meta, hidden: int, group: int, bits: int, out=None):
 
 def allreduce_sim_cmeta(x, group: int, bits_rs: int, bits_ag: int, out=None, workspace=None):
     """fc_allreduce_sim_cmeta.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
-    need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
-    if need == 0 and t != 0:
-        _check(lib().fc_allreduce_sim_cmeta(None, n, t, h, group, bits_rs, bits_ag, None, None, 0, None),
-               "fc_allreduce_sim_cmeta")
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
-    _check(lib().fc_allreduce_sim_cmeta(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, y.data_ptr(),
-                                        workspace.data_ptr(), workspace.numel(), _stream()),
-           "fc_allreduce_sim_cmeta")
-    return y
+    return _sim("fc_allreduce_sim_cmeta", x, group, bits_rs, bits_ag, out, workspace)
 
 
 # ---- FP8 E4M3 variant: one E4M3 byte per element, scales only ----
@@ -402,17 +406,9 @@ def allreduce_sim_cmeta(x, group: int, bits_rs: int, bits_ag: int, out=None, wor
 def quantize_fp8(x, group: int, out=None):
     """fc_quantize_fp8.  x: float16 [tokens, hidden] -> (E4M3 bytes u8 [tokens, hidden],
     scales f32 [tokens, hidden/group])."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    t, h = x.shape
-    if out is None:
-        if group <= 0 or h % group:
-            _check(lib().fc_quantize_fp8(None, t, h, group, None, None, None), "fc_quantize_fp8")
-        codes = torch.empty((t, h), dtype=torch.uint8, device=x.device)
-        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
-    else:
-        codes, scales = out
-        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    t, h = _x2(x)
+    _geometry("fc_quantize_fp8", h, group)
+    codes, scales = _coded_outputs(x.device, t, h, group, 8, out, [_f32("scales")])
     _check(lib().fc_quantize_fp8(x.data_ptr(), t, h, group, codes.data_ptr(), scales.data_ptr(), _stream()),
            "fc_quantize_fp8")
     return codes, scales
@@ -420,20 +416,9 @@ def quantize_fp8(x, group: int, out=None):
 
 def dequant_reduce_requant_fp8(codes_in, scales_in, hidden: int, group: int, out=None):
     """fc_dequant_reduce_requant_fp8.  codes_in u8 [N, tokens, hidden], scales_in f32 [N, tokens, hidden/group]."""
-    torch = _torch()
-    _dev(codes_in, torch.uint8, "codes_in"); _dev(scales_in, torch.float32, "scales_in")
-    n, t = codes_in.shape[0], codes_in.shape[1]
-    if out is None:
-        if group <= 0 or hidden % group:
-            _check(lib().fc_dequant_reduce_requant_fp8(None, 0, None, 0, n, t, hidden, group, None, None, None),
-                   "fc_dequant_reduce_requant_fp8")
-        codes = torch.empty((t, hidden), dtype=torch.uint8, device=codes_in.device)
-        scales = torch.empty((t, hidden // group), dtype=torch.float32, device=codes_in.device)
-    else:
-        codes, scales = out
-        _dev(codes, torch.uint8, "codes_out"); _dev(scales, torch.float32, "scales_out")
-    cstride = codes_in.stride(0) if n > 1 else 0
-    mstride = scales_in.stride(0) if n > 1 else 0
+    _geometry("fc_dequant_reduce_requant_fp8", hidden, group)
+    n, t, cstride, mstride = _stacked_inputs(codes_in, (scales_in,), hidden, group, 8, [_f32("scales_in")])
+    codes, scales = _coded_outputs(codes_in.device, t, hidden, group, 8, out, [_f32("scales")])
     _check(lib().fc_dequant_reduce_requant_fp8(
         codes_in.data_ptr(), cstride, scales_in.data_ptr(), mstride, n, t, hidden, group,
         codes.data_ptr(), scales.data_ptr(), _stream()), "fc_dequant_reduce_requant_fp8")
@@ -442,11 +427,9 @@ def dequant_reduce_requant_fp8(codes_in, scales_in, hidden: int, group: int, out
 
 def dequantize_fp8(codes, scales, hidden: int, group: int, out=None):
     """fc_dequantize_fp8 -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
-    t = codes.shape[0]
-    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
-    _dev(y, torch.float16, "y")
+    _geometry("fc_dequantize_fp8", hidden, group)
+    t = _coded_inputs(codes, (scales,), hidden, group, 8, [_f32("scales")])
+    y = _y_out(codes.device, t, hidden, out)
     _check(lib().fc_dequantize_fp8(codes.data_ptr(), scales.data_ptr(), t, hidden, group, y.data_ptr(),
                                    _stream()), "fc_dequantize_fp8")
     return y
@@ -454,20 +437,7 @@ def dequantize_fp8(codes, scales, hidden: int, group: int, out=None):
 
 def allreduce_sim_fp8(x, group: int, out=None, workspace=None):
     """fc_allreduce_sim_fp8.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
-    need = allreduce_sim_workspace_bytes(n, t, h, group, 8, 8)
-    if need == 0 and t != 0:
-        _check(lib().fc_allreduce_sim_fp8(None, n, t, h, group, None, None, 0, None), "fc_allreduce_sim_fp8")
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
-    _check(lib().fc_allreduce_sim_fp8(x.data_ptr(), n, t, h, group, y.data_ptr(), workspace.data_ptr(),
-                                      workspace.numel(), _stream()), "fc_allreduce_sim_fp8")
-    return y
+    return _sim("fc_allreduce_sim_fp8", x, group, 8, 8, out, workspace, bits_args=False)
 
 
 # ---- Hadamard rotation fused into the first quantization and the last dequantization ----
@@ -475,39 +445,27 @@ def allreduce_sim_fp8(x, group: int, out=None, workspace=None):
 def quantize_rot(x, group: int, bits: int, quantizer: int = QUANTIZER_ASYM, out=None):
     """fc_quantize_rot.  x: float16 [tokens, hidden] -> (codes, scales, zeros); zeros is None
     unless quantizer == QUANTIZER_ASYM."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    t, h = x.shape
+    t, h = _x2(x)
+    _geometry("fc_quantize_rot", h, group, bits)
     asym = quantizer == QUANTIZER_ASYM
-    if out is None:
-        if bits not in (4, 8) or group <= 0 or h % group:
-            _check(lib().fc_quantize_rot(None, t, h, group, bits, quantizer, None, None, None, None),
-                   "fc_quantize_rot")
-        codes = torch.empty((t, h * bits // 8), dtype=torch.uint8, device=x.device)
-        scales = torch.empty((t, h // group), dtype=torch.float32, device=x.device)
-        zeros = torch.empty_like(scales) if asym else None
-    else:
-        codes, scales, zeros = out
-        _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
-        if asym:
-            _dev(zeros, torch.float32, "zeros")
+    if out is not None and not asym:
+        out = tuple(out)[:2]
+    res = _coded_outputs(x.device, t, h, group, bits, out, [_f32("scales")] + ([_f32("zeros")] if asym else []))
+    codes, scales, zeros = res[0], res[1], (res[2] if asym else None)
     _check(lib().fc_quantize_rot(x.data_ptr(), t, h, group, bits, quantizer, codes.data_ptr(),
                                  scales.data_ptr(), zeros.data_ptr() if asym else None, _stream()),
            "fc_quantize_rot")
-    return codes, scales, (zeros if asym else None)
+    return codes, scales, zeros
 
 
 def dequantize_rot(codes, scales, zeros, hidden: int, group: int, bits: int,
                    quantizer: int = QUANTIZER_ASYM, out=None):
     """fc_dequantize_rot -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(codes, torch.uint8, "codes"); _dev(scales, torch.float32, "scales")
+    _geometry("fc_dequantize_rot", hidden, group, bits)
     asym = quantizer == QUANTIZER_ASYM
-    if asym:
-        _dev(zeros, torch.float32, "zeros")
-    t = codes.shape[0]
-    y = out if out is not None else torch.empty((t, hidden), dtype=torch.float16, device=codes.device)
-    _dev(y, torch.float16, "y")
+    metas = (scales, zeros) if asym else (scales,)
+    t = _coded_inputs(codes, metas, hidden, group, bits, [_f32("scales"), _f32("zeros")][:len(metas)])
+    y = _y_out(codes.device, t, hidden, out)
     _check(lib().fc_dequantize_rot(codes.data_ptr(), scales.data_ptr(), zeros.data_ptr() if asym else None,
                                    t, hidden, group, bits, quantizer, y.data_ptr(), _stream()),
            "fc_dequantize_rot")
@@ -517,29 +475,32 @@ def dequantize_rot(codes, scales, zeros, hidden: int, group: int, bits: int,
 def allreduce_sim_rot(x, group: int, bits_rs: int, bits_ag: int, quantizer: int = QUANTIZER_ASYM,
                       out=None, workspace=None):
     """fc_allreduce_sim_rot.  x: float16 [N, tokens, hidden] -> float16 [tokens, hidden]."""
-    torch = _torch()
-    _dev(x, torch.float16, "x")
-    n, t, h = x.shape
-    need = allreduce_sim_workspace_bytes(n, t, h, group, bits_rs, bits_ag)
-    if need == 0 and t != 0:
-        _check(lib().fc_allreduce_sim_rot(None, n, t, h, group, bits_rs, bits_ag, quantizer, None, None, 0,
-                                          None), "fc_allreduce_sim_rot")
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
-    y = out if out is not None else torch.empty((t, h), dtype=torch.float16, device=x.device)
-    _dev(y, torch.float16, "y")
-    _check(lib().fc_allreduce_sim_rot(x.data_ptr(), n, t, h, group, bits_rs, bits_ag, quantizer,
-                                      y.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
-           "fc_allreduce_sim_rot")
-    return y
+    return _sim("fc_allreduce_sim_rot", x, group, bits_rs, bits_ag, out, workspace, extra=(quantizer,))
+
+
+# ---- measurement aid (libfc_bench.so, include/fc_bench.h): not part of the product library ----
+
+def bench_lib() -> ctypes.CDLL:
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(_BENCH_LIB_PATH):
+            raise ImportError("%s not found: build it with `python -m paper_2412_04964_amd.build`" % _BENCH_LIB_PATH)
+        L = ctypes.CDLL(_BENCH_LIB_PATH)
+        L.fc_stream_reference.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                          ctypes.c_void_p, ctypes.c_void_p]
+        L.fc_stream_reference.restype = ctypes.c_int
+        _bench_lib = L
+    return _bench_lib
 
 
 def stream_reference(src, out):
-    """fc_stream_reference (measurement aid): src u8 [N, bytes], out u8 [bytes] = XOR over the N rows."""
+    """fc_stream_reference: src u8 [N, bytes], out u8 [bytes] = XOR over the N rows."""
     torch = _torch()
     _dev(src, torch.uint8, "src"); _dev(out, torch.uint8, "out")
-    n, nbytes = src.shape[0], src[0].numel()
-    _check(lib().fc_stream_reference(src.data_ptr(), src.stride(0) if n > 1 else 0, n, nbytes, out.data_ptr(),
-                                     _stream()), "fc_stream_reference")
+    if src.dim() != 2 or not 1 <= src.shape[0] <= FC_MAX_SRC:
+        raise ValueError("src must be u8 [n_src, bytes] with 1 <= n_src <= %d" % FC_MAX_SRC)
+    n, nbytes = src.shape
+    _shape(out, (nbytes,), "out")
+    _check(bench_lib().fc_stream_reference(src.data_ptr(), src.stride(0) if n > 1 else 0, n, nbytes, out.data_ptr(),
+                                           _stream()), "fc_stream_reference")
     return out

@@ -25,6 +25,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfc.so")
+BENCH_LIB = os.path.join(HERE, "libfc_bench.so")      # measurement aid (include/fc_bench.h), not the product
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
@@ -39,6 +40,7 @@ FLAGS = [
 # (source, object suffix, extra defines)
 UNITS = [("fc_api.hip", "api", []), ("fc_codec.hip", "codec", []), ("fc_wide.hip", "wide", []),
          ("fc_rot.hip", "rot", [])]
+BENCH_UNITS = [("fc_bench.hip", "bench", [])]
 for _bi in (4, 8):
     for _bo in (4, 8):
         UNITS.append(("fc_fused.hip", "fused_%d_%d" % (_bi, _bo),
@@ -61,18 +63,19 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(jobs) as ex:
-        results = list(ex.map(_compile, UNITS))
-    objs = [o for o, _ in results]
+        results = list(ex.map(_compile, UNITS + BENCH_UNITS))
     if verbose:
         for _, w in results:
             if w:
                 print(w, file=sys.stderr)
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC, "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s" % r.stderr)
-    os.replace(tmp, LIB)
+    objs = [o for o, _ in results]
+    for lib, members in ((LIB, objs[:len(UNITS)]), (BENCH_LIB, objs[len(UNITS):])):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        cmd = [HIPCC, "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp, *members]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s" % r.stderr)
+        os.replace(tmp, lib)
     return LIB
 
 

@@ -487,23 +487,6 @@ int fc_allreduce_sim_rot(const void *x_f16, int n_src, int64_t tokens, int64_t h
                                bits_ag, y_f16, hip_stream);
 }
 
-int fc_stream_reference(const void *in, int64_t in_src_stride_bytes, int n_src, int64_t bytes, void *out,
-                        void *hip_stream)
-{
-    if (n_src < 1 || n_src > FC_MAX_SRC || bytes < 0 || (bytes & 15) != 0 || bytes > (kMaxElems)) return FC_ERR_SHAPE;
-    if (bytes == 0) return FC_OK;
-    if (!in || !out) return FC_ERR_NULL;
-    if (n_src > 1) {
-        if (in_src_stride_bytes < bytes) return FC_ERR_SHAPE;
-        if ((in_src_stride_bytes & 15) != 0) return FC_ERR_ALIGN;
-    } else {
-        in_src_stride_bytes = 0;
-    }
-    if (!aligned16(in) || !aligned16(out)) return FC_ERR_ALIGN;
-    return hip_result(fc::launch_stream_reference(in, in_src_stride_bytes, n_src, bytes, out,
-                                                  static_cast<hipStream_t>(hip_stream)));
-}
-
 const char *fc_strerror(int code)
 {
     switch (code) {

@@ -1,0 +1,80 @@
+// fc_bench.hip -- measurement aid, built into its own shared library (libfc_bench.so, declared in
+// include/fc_bench.h) so that the product library exports the method's entry points only.
+//
+// fc_stream_reference: the memory access pattern of the fused Dequantize x N -> ReduceSum ->
+// FinegrainedQuantize kernel with the arithmetic and the scales / zero-points taken out.
+#include "fc_bench.h"
+
+#include "fc_device.hpp"
+#include "fc_launch.hpp"
+
+namespace fc {
+
+// NSRC input streams of `bytes` each, one output stream, out = XOR of the inputs; same 4 KB tile per
+// workgroup, buffer-to-LDS staging, tile dealing and cache policy as k_dequant_reduce_requant.
+template <int NSRC>
+__global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(const uint8_t *__restrict__ in, int64_t in_stride,
+                                                   int64_t bytes, uint8_t *__restrict__ out)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t landing[fused_block_threads(1) / 64][NSRC][1024];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    constexpr int kTileBytes = fused_block_threads(1) * 16;
+    const int64_t b_tile = (int64_t)xcd_tile((u32)((bytes + kTileBytes - 1) / kTileBytes)) * kTileBytes;
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) {
+        const rsrc_t r = make_rsrc(in + (int64_t)j * in_stride + b_tile, bytes - b_tile);
+        dma_piece(r, tid * 16, &landing[wave][j][0]);
+    }
+    issue_order_fence();
+    u32x4 acc = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) {
+        wait_vmem_outstanding(NSRC - 1 - j);
+        u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+        lds_read_complete(a);
+        acc ^= a;
+    }
+    const rsrc_t ro = make_rsrc(out + b_tile, bytes - b_tile);
+    __builtin_amdgcn_raw_buffer_store_b128(acc, ro, tid * 16, 0, kStreamPolicy);
+}
+
+template <int NSRC>
+static hipError_t launch_sr(dim3 grid, hipStream_t stream, const uint8_t *in, int64_t in_stride, int64_t bytes, uint8_t *out)
+{
+    return launch_kernel(k_stream_reference<NSRC>, grid, dim3(fused_block_threads(1)), stream, in, in_stride, bytes, out);
+}
+
+}  // namespace fc
+
+extern "C" int fc_stream_reference(const void *in, int64_t in_src_stride_bytes, int n_src, int64_t bytes, void *out,
+                                   void *hip_stream)
+{
+    const auto aligned16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    if (n_src < 1 || n_src > 8 || bytes < 0 || (bytes & 15) != 0 || bytes > ((int64_t)1 << 36)) return -4;
+    if (bytes == 0) return 0;
+    if (!in || !out) return -1;
+    if (n_src > 1) {
+        if (in_src_stride_bytes < bytes) return -4;
+        if ((in_src_stride_bytes & 15) != 0) return -5;
+    } else {
+        in_src_stride_bytes = 0;
+    }
+    if (!aligned16(in) || !aligned16(out)) return -5;
+    const uint8_t *i = static_cast<const uint8_t *>(in);
+    uint8_t *o = static_cast<uint8_t *>(out);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t tile = fc::fused_block_threads(1) * 16;
+    const dim3 grid((unsigned)((bytes + tile - 1) / tile));
+    hipError_t e = hipErrorInvalidValue;
+    switch (n_src) {
+    case 1: e = fc::launch_sr<1>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 2: e = fc::launch_sr<2>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 3: e = fc::launch_sr<3>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 4: e = fc::launch_sr<4>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 5: e = fc::launch_sr<5>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 6: e = fc::launch_sr<6>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 7: e = fc::launch_sr<7>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    case 8: e = fc::launch_sr<8>(grid, stream, i, in_src_stride_bytes, bytes, o); break;
+    }
+    return e == hipSuccess ? 0 : -7;
+}

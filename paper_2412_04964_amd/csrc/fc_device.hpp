@@ -1230,34 +1230,4 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequantize(
     }
 }
 
-// Measurement aid (not part of the method): the fused kernel's memory access
-// pattern with no arithmetic.  NSRC input streams of `bytes` each, one output
-// stream, out = XOR of the inputs; same 4 KB tile per workgroup, buffer-to-LDS
-// staging, tile dealing and cache policy as k_dequant_reduce_requant.
-template <int NSRC>
-__global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(const uint8_t *__restrict__ in, int64_t in_stride,
-                                                   int64_t bytes, uint8_t *__restrict__ out)
-{
-    __shared__ __attribute__((aligned(16))) uint8_t landing[fused_block_threads(1) / 64][NSRC][1024];
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    constexpr int kTileBytes = fused_block_threads(1) * 16;
-    const int64_t b_tile = (int64_t)xcd_tile((u32)((bytes + kTileBytes - 1) / kTileBytes)) * kTileBytes;
-#pragma unroll
-    for (int j = 0; j < NSRC; ++j) {
-        const rsrc_t r = make_rsrc(in + (int64_t)j * in_stride + b_tile, bytes - b_tile);
-        dma_piece(r, tid * 16, &landing[wave][j][0]);
-    }
-    issue_order_fence();
-    u32x4 acc = u32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int j = 0; j < NSRC; ++j) {
-        wait_vmem_outstanding(NSRC - 1 - j);
-        u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
-        lds_read_complete(a);
-        acc ^= a;
-    }
-    const rsrc_t ro = make_rsrc(out + b_tile, bytes - b_tile);
-    __builtin_amdgcn_raw_buffer_store_b128(acc, ro, tid * 16, 0, kStreamPolicy);
-}
-
 }  // namespace fc

@@ -21,49 +21,39 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
     const int64_t blocks = (a.n_elems + tile - 1) / tile;
 #if FC_BITS_IN == 8 && FC_BITS_OUT == 8
     if (a.codec == CODEC_FP8) {
-        k_dequant_reduce_requant_sym<8, 8, NSRC, LPG, true>
-            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
+        return launch_kernel(k_dequant_reduce_requant_sym<8, 8, NSRC, LPG, true>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
                 a.n_elems, a.group / lane_elems(8), log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
-        return hipGetLastError();
     }
 #endif
     if (a.codec == CODEC_SYM) {
-        k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
-            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
+        return launch_kernel(k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
                 a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
-        return hipGetLastError();
     }
     if (a.codec == CODEC_ASYMH) {
-        k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, true>
-            <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
+        return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, true>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, nullptr,
                 a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out, nullptr);
-        return hipGetLastError();
     }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
     if constexpr (LPG == 128 / lane_elems(FC_BITS_IN)) {     // g = 128: small volumes in single-wavefront workgroups
         const int64_t wave_elems = 64 * lane_elems(FC_BITS_IN);
         const int64_t waves = (a.n_elems + wave_elems - 1) / wave_elems;
         if (waves <= kSmallLaunchWaves) {
-            k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, false, 64>
-                <<<dim3((unsigned)waves), dim3(64), 0, stream>>>(
+            return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, false, 64>, dim3((unsigned)waves), dim3(64), stream,
                     static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
                     a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
                     static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
-            return hipGetLastError();
         }
     }
-    k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>
-        <<<dim3((unsigned)blocks), dim3(BT), 0, stream>>>(
+    return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>, dim3((unsigned)blocks), dim3(BT), stream,
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
             a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
             static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
-    return hipGetLastError();
 }
 
 // groups spanning 1, 2, 4 or 8 lanes get their own instantiation; larger

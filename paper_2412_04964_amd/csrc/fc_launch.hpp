@@ -5,7 +5,29 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 namespace fc {
+
+// Launch `kernel` and return the status of THIS launch.  (The <<< >>> syntax reports failures only
+// through the thread's last-error slot, which hipGetLastError would also clear of errors that other
+// code left there, and a stale one would be taken for a failure of a launch that succeeded.)
+template <typename... P, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t stream,
+                                     std::tuple<P...> &args, std::index_sequence<I...>)
+{
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(args))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, stream);
+}
+
+template <typename... P, typename... A>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t stream, A... a)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    std::tuple<P...> args{static_cast<P>(a)...};
+    return launch_kernel_impl(kernel, grid, block, stream, args, std::index_sequence_for<P...>{});
+}
 
 // Quantizer: 0 = asymmetric (Eq. 1-2), 1 = symmetric (Eq. 3-4), 2 = FP8 E4M3 (8 bit only),
 // 3 = asymmetric with binary16 metadata (one 32-bit word per group, passed where the other
@@ -58,10 +80,6 @@ hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t t
                                void *codes, float *scales, float *zeros, hipStream_t stream);
 hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,
                                  int64_t tokens, int hidden, int group, void *y_f16, hipStream_t stream);
-
-// measurement aid: n_src streams of `bytes` in, one out, the fused kernel's access pattern without arithmetic
-hipError_t launch_stream_reference(const void *in, int64_t in_stride, int n_src, int64_t bytes, void *out,
-                                   hipStream_t stream);
 
 inline int log2_int(int v)
 {

@@ -302,9 +302,8 @@ template <int BITS, int CODEC, int LOGH>
 hipError_t quantize_rot_one(const uint16_t *x, int64_t tokens, int group, uint8_t *c, float *scales,
                             float *zeros, hipStream_t stream)
 {
-    k_quantize_rot<BITS, CODEC, LOGH><<<dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T), 0, stream>>>(
-        x, group / lane_elems(BITS), log2_int(group), c, scales, zeros);
-    return hipGetLastError();
+    return launch_kernel(k_quantize_rot<BITS, CODEC, LOGH>, dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T),
+                         stream, x, group / lane_elems(BITS), log2_int(group), c, scales, zeros);
 }
 
 template <int BITS, int CODEC>
@@ -323,9 +322,8 @@ template <int BITS, int CODEC, int LOGH>
 hipError_t dequantize_rot_one(const uint8_t *c, const float *scales, const float *zeros, int64_t tokens,
                               int group, uint16_t *y, hipStream_t stream)
 {
-    k_dequantize_rot<BITS, CODEC, LOGH><<<dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T), 0, stream>>>(
-        c, scales, zeros, log2_int(group), y);
-    return hipGetLastError();
+    return launch_kernel(k_dequantize_rot<BITS, CODEC, LOGH>, dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T),
+                         stream, c, scales, zeros, log2_int(group), y);
 }
 
 template <int BITS, int CODEC>

@@ -269,17 +269,14 @@ hipError_t quantize_wide_bits(const uint16_t *x, int64_t n_elems, int group, uin
     const WideShape w = wide_shape(BITS, group);
     const dim3 grid((unsigned)(n_elems / group)), block(w.threads);
     switch (w.p) {
-    case 1: k_quantize_wide<BITS, 1, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
-    case 2: k_quantize_wide<BITS, 2, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros); break;
+    case 1: return launch_kernel(k_quantize_wide<BITS, 1, CODEC>, grid, block, stream, x, group, c, scales, zeros);
+    case 2: return launch_kernel(k_quantize_wide<BITS, 2, CODEC>, grid, block, stream, x, group, c, scales, zeros);
     case 4:
-        if constexpr (BITS == 8) {
-            k_quantize_wide<BITS, 4, CODEC><<<grid, block, 0, stream>>>(x, group, c, scales, zeros);
-            break;
-        }
+        if constexpr (BITS == 8)
+            return launch_kernel(k_quantize_wide<BITS, 4, CODEC>, grid, block, stream, x, group, c, scales, zeros);
         [[fallthrough]];
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 template <int BI, int BO, int CODEC>
@@ -289,23 +286,18 @@ hipError_t fused_wide_bits(const FusedArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(a.n_elems / a.group)), block(w.threads);
     const uint8_t *ci = static_cast<const uint8_t *>(a.codes_in);
     uint8_t *co = static_cast<uint8_t *>(a.codes_out);
-#define FC_WIDE_LAUNCH(PP)                                                                               \
-    k_dequant_reduce_requant_wide<BI, BO, PP, CODEC><<<grid, block, 0, stream>>>(                          \
-        ci, a.codes_stride, a.scales_in, a.zeros_in, a.meta_stride, a.n_src, a.group, co, a.scales_out, \
-        a.zeros_out)
+#define FC_WIDE_LAUNCH(PP)                                                                                  \
+    launch_kernel(k_dequant_reduce_requant_wide<BI, BO, PP, CODEC>, grid, block, stream, ci, a.codes_stride, \
+                  a.scales_in, a.zeros_in, a.meta_stride, a.n_src, a.group, co, a.scales_out, a.zeros_out)
     switch (w.p) {
-    case 1: FC_WIDE_LAUNCH(1); break;
-    case 2: FC_WIDE_LAUNCH(2); break;
+    case 1: return FC_WIDE_LAUNCH(1);
+    case 2: return FC_WIDE_LAUNCH(2);
     case 4:
-        if constexpr (BI == 8) {
-            FC_WIDE_LAUNCH(4);
-            break;
-        }
+        if constexpr (BI == 8) return FC_WIDE_LAUNCH(4);
         [[fallthrough]];
     default: return hipErrorInvalidValue;
     }
 #undef FC_WIDE_LAUNCH
-    return hipGetLastError();
 }
 
 }  // namespace

@@ -18,8 +18,8 @@ def L():
     return fc.lib()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "fc.h")).read()
+def declared_functions(header="fc.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fc_[a-z_0-9]+)\s*\(", text)))
 
@@ -149,6 +149,18 @@ def test_variant_entry_points_argument_checks(L):
     assert L.fc_allreduce_sim_cmeta(P, 9, 16, 4096, 128, 4, 4, P, P, need, None) == -4
 
 
+def test_bench_library_exports_exactly_its_header_and_the_product_library_none_of_it(L):
+    import subprocess
+    import paper_2412_04964_amd as fc
+    B = fc.bench_lib()
+    names = declared_functions("fc_bench.h")
+    assert names == ["fc_stream_reference"]
+    out = subprocess.run(["nm", "-D", "--defined-only", B._name], capture_output=True, text=True).stdout
+    assert sorted(l.split()[-1] for l in out.splitlines() if " T " in l) == names
+    assert not hasattr(L, "fc_stream_reference")
+    assert "fc_stream_reference" not in declared_functions()
+
+
 def test_rotation_and_stream_reference_argument_checks(L):
     q = L.fc_quantize_rot
     assert q(P, 4, 1024, 128, 4, 0, P, P, P, None) == -4          # hidden must be 2048, 4096 or 8192
@@ -166,7 +178,8 @@ def test_rotation_and_stream_reference_argument_checks(L):
     assert s(P, 4, 16, 4096, 128, 4, 8, 0, P, P, need - 1, None) == -6
     assert s(P, 4, 16, 4096, 128, 4, 8, 2, P, P, need, None) == -2
     assert s(P, 4, 16, 2560, 128, 4, 8, 0, P, P, need, None) == -4
-    r = L.fc_stream_reference
+    import paper_2412_04964_amd as fc
+    r = fc.bench_lib().fc_stream_reference
     assert r(P, 4096, 4, 4096 + 8, P, None) == -4                 # bytes % 16
     assert r(P, 2048, 4, 4096, P, None) == -4                     # sources would overlap
     assert r(P, 4096, 0, 4096, P, None) == -4
@@ -201,3 +214,93 @@ def test_missing_library_fails_loudly():
     env = dict(os.environ, FC_LIBRARY="/nonexistent/libfc.so", PYTHONPATH=ROOT)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, cwd=ROOT)
     assert r.returncode == 3 and "no CPU fallback" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
+def test_binding_checks_every_tensor_against_the_geometry_before_the_c_call(monkeypatch):
+    # The kernels take their buffer ranges from (tokens, hidden, group, bits): a tensor that disagrees with them
+    # must be refused on the host.  CPU tensors stand in for device tensors here (the device check is switched
+    # off) and the C library is replaced by an object that fails the test when any entry point is reached.
+    torch = pytest.importorskip("torch")
+    from paper_2412_04964_amd import binding as b
+
+    class Unreachable:
+        def __getattr__(self, name):
+            if name in ("fc_strerror",):
+                return lambda code: b"x"
+            if name == "fc_last_hip_error":
+                return lambda: 0
+            if name == "fc_allreduce_sim_workspace_bytes":
+                return lambda *a: 1 << 20
+            raise AssertionError("C entry point %s reached with inconsistent tensors" % name)
+
+    def dev(t, dtype, what):
+        if t.dtype != dtype:
+            raise TypeError(what)
+        return t
+
+    monkeypatch.setattr(b, "_dev", dev)
+    monkeypatch.setattr(b, "lib", lambda: Unreachable())
+    monkeypatch.setattr(b, "bench_lib", lambda: Unreachable())
+    monkeypatch.setattr(b, "_stream", lambda: 0)
+    f16, u8, f32, i32 = torch.float16, torch.uint8, torch.float32, torch.int32
+    T, H, G = 4, 256, 128
+    x = torch.zeros(T, H, dtype=f16)
+    codes4 = torch.zeros(T, H // 2, dtype=u8); codes8 = torch.zeros(T, H, dtype=u8)
+    meta = torch.zeros(T, H // G, dtype=f32)
+    y = torch.zeros(T, H, dtype=f16)
+
+    bad = pytest.raises(ValueError)
+    with bad: b.quantize(x, G, 4, out=(codes8, meta, meta))                     # codes sized for 8 bit
+    with bad: b.quantize(x, G, 4, out=(codes4, meta[:, :1], meta))              # too few scales
+    with bad: b.quantize(x, G, 4, out=(codes4, meta, meta[:3]))                 # too few rows of zero-points
+    with bad: b.quantize(x.view(-1), G, 4)                                      # not [tokens, hidden]
+    with bad: b.quantize_sym(x, G, 8, out=(codes4, meta))
+    with bad: b.quantize_fp8(x, G, out=(codes4, meta))
+    with bad: b.quantize_cmeta(x, G, 4, out=(codes4, torch.zeros(T, 1, dtype=i32)))
+    with bad: b.quantize_rot(x, G, 4, out=(codes8, meta, meta))
+    with bad: b.dequantize(codes4, meta, meta, H, G, 8)                         # bits disagree with the codes
+    with bad: b.dequantize(codes4, meta, meta, 2 * H, G, 4)                     # hidden disagrees
+    with bad: b.dequantize(codes4, meta, meta[:, :1], H, G, 4)
+    with bad: b.dequantize(codes4, meta, meta, H, G, 4, out=y[:2])              # short output
+    with bad: b.dequantize_sym(codes8, meta, H, G, 4)
+    with bad: b.dequantize_fp8(codes4, meta, H, G)
+    with bad: b.dequantize_cmeta(codes4, torch.zeros(T, 1, dtype=i32), H, G, 4)
+    with bad: b.dequantize_rot(codes4, meta, meta[:2], H, G, 4)
+    c_in = torch.zeros(3, T, H // 2, dtype=u8); m_in = torch.zeros(3, T, H // G, dtype=f32)
+    with bad: b.dequant_reduce_requant(c_in, m_in, m_in, H, G, 8, 8)            # bits_in disagrees with the codes
+    with bad: b.dequant_reduce_requant(c_in, m_in[:2], m_in, H, G, 4, 4)        # fewer scale slabs than sources
+    with bad: b.dequant_reduce_requant(c_in, m_in, m_in[:, :2], H, G, 4, 4)
+    with bad: b.dequant_reduce_requant(c_in, m_in, m_in, H, G, 4, 8, out=(codes4, meta, meta))   # out sized for 4 bit
+    with bad: b.dequant_reduce_requant(c_in[0], m_in[0], m_in[0], H, G, 4, 4)   # missing source axis
+    with bad: b.dequant_reduce_requant_sym(c_in, m_in[:, :, :1], H, G, 4, 4)
+    with bad: b.dequant_reduce_requant_fp8(c_in, m_in, H, G)
+    with bad: b.dequant_reduce_requant_cmeta(c_in, torch.zeros(3, T, 1, dtype=i32), H, G, 4, 4)
+    x3 = torch.zeros(2, T, H, dtype=f16)
+    with bad: b.allreduce_sim(x3, G, 4, 4, out=y[:, :128])
+    with bad: b.allreduce_sim(x, G, 4, 4)                                       # missing source axis
+    with bad: b.allreduce_sim_static(x3, G, 4, 4, out=y[:3])
+    with pytest.raises(b.FcError): b.allreduce_sim(x3, G, 4, 4, workspace=torch.zeros(16, dtype=u8))   # short workspace
+    with pytest.raises(b.FcError): b.allreduce_sim(torch.zeros(9, T, H, dtype=f16), G, 4, 4)           # too many sources
+    with bad: b.stream_reference(torch.zeros(2, 64, dtype=u8), torch.zeros(48, dtype=u8))
+    # argument errors keep the C library's codes
+    for call, code in ((lambda: b.quantize(x, G, 5), -2), (lambda: b.quantize(x, 96, 4), -3),
+                       (lambda: b.quantize(x, 512, 4), -3), (lambda: b.dequantize(codes4, meta, meta, H, 16, 4), -3)):
+        with pytest.raises(b.FcError) as ei:
+            call()
+        assert ei.value.code == code
+    with pytest.raises(TypeError): b.quantize(x.float(), G, 4)
+
+
+def test_binding_refuses_tensors_of_another_device(monkeypatch):
+    # the C ABI works on the device that is current on the calling thread; a tensor of another device is refused
+    torch = pytest.importorskip("torch")
+    from paper_2412_04964_amd import binding as b
+
+    class OnDevice1(torch.Tensor):
+        is_cuda = property(lambda self: True)
+        device = property(lambda self: torch.device("cuda", 1))
+
+    monkeypatch.setattr(torch.cuda, "current_device", lambda: 0)
+    fake = torch.zeros(2, 2, dtype=torch.float16).as_subclass(OnDevice1)
+    with pytest.raises(ValueError, match="current device"):
+        b._dev(fake, torch.float16, "x")

@@ -407,6 +407,53 @@ def test_full_size_configs_on_sampled_rows(fc, name):
     assert bool((zo == torch.round(zo)).all())
 
 
+def _by_row_blocks(fn, n_rows, blocks=16):
+    """fn(r0, r1) on contiguous row blocks in host threads (the oracle is scalar C; ctypes drops the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+    edges = np.linspace(0, n_rows, min(blocks, n_rows) + 1).astype(int)
+    with ThreadPoolExecutor(8) as ex:
+        return list(ex.map(lambda k: fn(int(edges[k]), int(edges[k + 1])), range(len(edges) - 1)))
+
+
+# every element of the benchmark volumes, all three stages, against the oracle (groups never cross token rows,
+# so the oracle runs on row blocks in parallel); the headline shape also on the other two seeds
+@pytest.mark.parametrize("name,seed", [("llama3_8b_prefill", 0), ("llama3_70b_prefill", 0), ("llama3_70b_prefill", 1),
+                                       ("llama3_70b_prefill", 2), ("wide_fanin", 0), ("decode", 0),
+                                       ("llama3_70b_prefill_int6", 0)])
+def test_full_size_configs_every_element(fc, name, seed):
+    w = synth_inputs.WORKLOADS[name]
+    x = synth_inputs.make_partials_device(w.n_src, w.tokens, w.hidden, seed, "cuda", w.outlier_frac, w.outlier_gain)
+    stage1 = [fc.quantize(x[j], w.group, w.bits_in) for j in range(w.n_src)]
+    c = torch.stack([p[0] for p in stage1]); s = torch.stack([p[1] for p in stage1])
+    z = torch.stack([p[2] for p in stage1])
+    del stage1
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, w.hidden, w.group, w.bits_in, w.bits_out)
+    y = fc.dequantize(co, so, zo, w.hidden, w.group, w.bits_out)
+    torch.cuda.synchronize()
+    xh = x.cpu().numpy()
+    got1 = (c.cpu().numpy(), s.cpu().numpy(), z.cpu().numpy())
+    got2 = (co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy())
+    goty = y.cpu().numpy()
+    del x, c, s, z, co, so, zo, y
+
+    def block(r0, r1):
+        o1 = oracle_stage1(xh[:, r0:r1], w.group, w.bits_in)
+        o2 = oracle.dequant_reduce_requant(*o1, w.hidden, w.group, w.bits_in, w.bits_out)
+        oy = oracle.dequantize(*o2, w.hidden, w.group, w.bits_out)
+        bad = []
+        for what, got, want in (("stage 1", tuple(g[:, r0:r1] for g in got1), o1),
+                                ("fused", tuple(g[r0:r1] for g in got2), o2)):
+            for part, g_, w_ in zip(("codes", "scales", "zeros"), got, want):
+                if not same_bits(g_, w_):
+                    bad.append("%s %s rows [%d,%d): %s" % (what, part, r0, r1, first_diff(g_, w_)))
+        if not same_bits(goty[r0:r1].view(np.uint16), oy.view(np.uint16)):
+            bad.append("output rows [%d,%d): %s" % (r0, r1, first_diff(goty[r0:r1].view(np.uint16), oy.view(np.uint16))))
+        return bad
+
+    bad = sum(_by_row_blocks(block, w.tokens), [])
+    assert not bad, "%s seed %d: %s" % (name, seed, "; ".join(bad[:4]))
+
+
 @pytest.mark.parametrize("variant", ["asym", "sym", "fp8", "cmeta", "rot"])
 def test_entry_points_capture_into_a_hip_graph_and_replay(fc, variant):
     # the library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so a

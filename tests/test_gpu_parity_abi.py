@@ -1,0 +1,126 @@
+"""Corners of the C ABI on the GPU, called raw through ctypes: per-source metadata slabs that are only
+4-byte aligned (odd source strides), on both ways the fused kernel fetches group parameters (the shared table
+for narrow groups, per-lane loads for wide ones), and the single-wavefront-workgroup launch that small volumes
+take, for every fan-in and bit-width pair.  Bit for bit against the CPU oracle.  Run with ``-m gpu``."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs
+from test_gpu_parity import Guarded, dev, first_diff, oracle_stage1, same_bits, fc  # noqa: F401
+from test_gpu_parity_cmeta import oracle_stage1_cmeta
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _padded_slabs(arrs, stride_elems, dtype, lead):
+    """The per-source arrays of `arrs` [N, ...] laid out `stride_elems` apart after `lead` elements of poison,
+    in one device buffer whose base is 16-byte aligned; returns (buffer, view of element `lead`)."""
+    n = arrs.shape[0]
+    per = arrs[0].size
+    assert stride_elems >= per
+    buf = torch.full((lead + n * stride_elems + 8,), -12345, dtype=dtype, device="cuda")
+    flat = torch.from_numpy(np.ascontiguousarray(arrs).reshape(n, per).view(
+        {torch.float32: np.float32, torch.int32: np.int32}[dtype])).cuda()
+    for j in range(n):
+        buf[lead + j * stride_elems: lead + j * stride_elems + per] = flat[j]
+    return buf, buf[lead:]
+
+
+@pytest.mark.parametrize("group", [32, 128, 512, 2048])
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8)])
+@pytest.mark.parametrize("n_src", [2, 5])
+def test_fused_with_odd_metadata_strides(fc, group, bits_in, bits_out, n_src):
+    # scales and zero-points of source j start at +j*stride floats with an odd stride, so slabs 1, 3, ... are
+    # only 4-byte aligned; base pointers stay 16-byte aligned as the header requires
+    t, h = 11, 4096
+    x = synth_inputs.make_partials(n_src, t, h, seed=300 + group + n_src, outlier_frac=0.01)
+    c, s, z = oracle_stage1(x, group, bits_in)
+    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+    per = t * h // group
+    for extra in (1, 3, 7):
+        stride = per + extra + (0 if (per + extra) % 2 else 1)            # odd number of floats
+        assert stride % 2 == 1
+        sbuf, sview = _padded_slabs(s, stride, torch.float32, 0)
+        zbuf, zview = _padded_slabs(z, stride, torch.float32, 0)
+        cd = dev(c)
+        co = Guarded((t, h * bits_out // 8), torch.uint8)
+        so = Guarded((t, h // group), torch.float32)
+        zo = Guarded((t, h // group), torch.float32)
+        rc = fc.lib().fc_dequant_reduce_requant(cd.data_ptr(), cd.stride(0), sview.data_ptr(), zview.data_ptr(), stride,
+                                                n_src, t, h, group, bits_in, bits_out, co.t.data_ptr(),
+                                                so.t.data_ptr(), zo.t.data_ptr(), _stream())
+        assert rc == 0
+        torch.cuda.synchronize()
+        for g_ in (co, so, zo):
+            g_.check()
+        for part, got, w_ in zip(("codes", "scales", "zeros"), (co, so, zo), want):
+            assert same_bits(got.t.cpu().numpy(), w_), "stride %d g=%d %s: %s" % (
+                stride, group, part, first_diff(got.t.cpu().numpy(), w_))
+
+
+@pytest.mark.parametrize("group", [128, 512])
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8)])
+def test_fused_cmeta_with_odd_metadata_strides(fc, group, bits_in, bits_out):
+    n_src, t, h = 3, 11, 4096
+    x = synth_inputs.make_partials(n_src, t, h, seed=500 + group, outlier_frac=0.01)
+    c, m = oracle_stage1_cmeta(x, group, bits_in)
+    want = oracle.dequant_reduce_requant_cmeta(c, m, h, group, bits_in, bits_out)
+    per = t * h // group
+    stride = per + (1 if per % 2 == 0 else 2)
+    mbuf, mview = _padded_slabs(m.view(np.int32), stride, torch.int32, 0)
+    cd = dev(c)
+    co = Guarded((t, h * bits_out // 8), torch.uint8)
+    mo = Guarded((t, h // group), torch.int32)
+    rc = fc.lib().fc_dequant_reduce_requant_cmeta(cd.data_ptr(), cd.stride(0), mview.data_ptr(), stride, n_src, t, h,
+                                                  group, bits_in, bits_out, co.t.data_ptr(), mo.t.data_ptr(), _stream())
+    assert rc == 0
+    torch.cuda.synchronize()
+    co.check(); mo.check()
+    assert same_bits(co.t.cpu().numpy(), want[0]), first_diff(co.t.cpu().numpy(), want[0])
+    assert same_bits(mo.t.cpu().numpy().view(np.uint32), want[1])
+
+
+def test_fused_rejects_misaligned_bases_and_short_strides(fc):
+    L = fc.lib()
+    t, h, g = 4, 1024, 128
+    c = torch.zeros((2, t, h // 2), dtype=torch.uint8, device="cuda")
+    s = torch.zeros((2 * t * h // g + 8,), dtype=torch.float32, device="cuda")
+    o = torch.zeros((t, h // 2), dtype=torch.uint8, device="cuda")
+    so = torch.zeros((t, h // g), dtype=torch.float32, device="cuda")
+    args = lambda sp, zp, ms: (c.data_ptr(), c.stride(0), sp, zp, ms, 2, t, h, g, 4, 4, o.data_ptr(), so.data_ptr(),
+                               so.data_ptr(), _stream())
+    assert L.fc_dequant_reduce_requant(*args(s.data_ptr() + 4, s.data_ptr(), t * h // g)) == -5      # base not 16-byte aligned
+    assert L.fc_dequant_reduce_requant(*args(s.data_ptr(), s.data_ptr(), t * h // g - 1)) == -4      # stride below one slab
+
+
+# The launcher gives asymmetric g = 128 volumes of at most 256 wavefront tiles single-wavefront workgroups:
+# every fan-in and bit-width pair, with a ragged last wavefront tile and rows that straddle tiles
+@pytest.mark.parametrize("bits_in,bits_out", [(8, 8), (4, 4), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_fused_small_volumes_every_fan_in(fc, bits_in, bits_out, n_src):
+    for (t, h) in [(7, 2176), (1, 128), (8, 8192), (31, 8192)]:
+        waves = -(-t * h // (64 * 128 // bits_in))
+        assert waves <= 256
+        x = synth_inputs.make_partials(n_src, t, h, seed=7 * n_src + bits_in + t, outlier_frac=0.02)
+        c, s, z = oracle_stage1(x, 128, bits_in)
+        want = oracle.dequant_reduce_requant(c, s, z, h, 128, bits_in, bits_out)
+        cd, sd, zd = dev(c), dev(s), dev(z)
+        co = Guarded((t, h * bits_out // 8), torch.uint8)
+        so = Guarded((t, h // 128), torch.float32)
+        zo = Guarded((t, h // 128), torch.float32)
+        rc = fc.lib().fc_dequant_reduce_requant(cd.data_ptr(), cd.stride(0), sd.data_ptr(), zd.data_ptr(), sd.stride(0),
+                                                n_src, t, h, 128, bits_in, bits_out, co.t.data_ptr(), so.t.data_ptr(),
+                                                zo.t.data_ptr(), _stream())
+        assert rc == 0
+        torch.cuda.synchronize()
+        for part, got, w_ in zip(("codes", "scales", "zeros"), (co, so, zo), want):
+            got.check()
+            assert same_bits(got.t.cpu().numpy(), w_), "N=%d %dx%d %d->%d %s: %s" % (
+                n_src, t, h, bits_in, bits_out, part, first_diff(got.t.cpu().numpy(), w_))

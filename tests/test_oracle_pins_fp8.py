@@ -240,3 +240,37 @@ def test_fp8_single_source_reduce_equals_dequantize_and_bad_arguments():
     assert np.array_equal(bits_of(acc), bits_of(oracle.dequantize_fp8_f32(c, s, 512, 64)))
     with pytest.raises(Exception):
         oracle.quantize_fp8(x, 96)
+
+
+def test_fp8_dequantize_to_binary16_against_the_format_table_and_numpy():
+    """The last step of the FP8 all-reduce (Appendix "FP8 and FP4 Format"; Algorithm 1, final Dequantize):
+    every byte decoded by the format's definition, times the scale of ITS group (rows, groups and scales all
+    different, so a wrong group or row index shows), one fp32 product, numpy's binary16 rounding."""
+    rng = np.random.default_rng(11)
+    t, h, g = 5, 384, 64
+    codes = rng.integers(0, 256, size=(t, h), dtype=np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x3C                               # the two NaN bytes are outside the domain
+    scales = np.exp(rng.uniform(-9, 7, size=(t, h // g))).astype(F32)
+    scales[1, 2] = F32(3.0e2)                                          # 448 * 300 overflows binary16
+    scales[3, 0] = F32(2.0 ** -20)                                     # binary16 subnormals
+    table = np.array([float(v) for v in E4M3] + [0.0], dtype=F32)      # index 127 unused
+    val = table[codes & 0x7F] * np.where(codes & 0x80, F32(-1), F32(1))
+    want32 = (val * np.repeat(scales, g, axis=1)).astype(F32)
+    with np.errstate(over="ignore"):
+        want16 = want32.astype(np.float16)
+    got32 = oracle.dequantize_fp8_f32(codes, scales, h, g)
+    assert np.array_equal(bits_of(got32), bits_of(want32))
+    got16 = oracle.dequantize_fp8(codes, scales, h, g)
+    assert got16.dtype == np.float16 and got16.shape == (t, h)
+    assert np.array_equal(got16.view(np.uint16), want16.view(np.uint16))
+    assert np.isinf(want16).any() and ((want16.view(np.uint16) & 0x7C00) == 0).any()
+    # -0 bytes keep their sign through the product and the rounding
+    z = np.full((1, 64), 0x80, np.uint8)
+    assert (oracle.dequantize_fp8(z, np.ones((1, 1), F32), 64, 64).view(np.uint16) == 0x8000).all()
+    # and the end-to-end function is the composition of the three pinned steps
+    x = synth_inputs.make_partials(3, 4, 512, seed=9, outlier_frac=0.02)
+    parts = [oracle.quantize_fp8(x[j], 128) for j in range(3)]
+    c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
+    co, so = oracle.dequant_reduce_requant_fp8(c, s, 512, 128)
+    assert np.array_equal(oracle.allreduce_sim_fp8(x, 128).view(np.uint16),
+                          oracle.dequantize_fp8(co, so, 512, 128).view(np.uint16))
