@@ -19,7 +19,7 @@ __global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(con
     __shared__ __attribute__((aligned(16))) uint8_t landing[fused_block_threads(1) / 64][NSRC][1024];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     constexpr int kTileBytes = fused_block_threads(1) * 16;
-    const int64_t b_tile = (int64_t)xcd_tile((u32)((bytes + kTileBytes - 1) / kTileBytes)) * kTileBytes;
+    const int64_t b_tile = (int64_t)xcd_tile<xcd_chunk(kTileBytes)>((u32)((bytes + kTileBytes - 1) / kTileBytes)) * kTileBytes;
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) {
         const rsrc_t r = make_rsrc(in + (int64_t)j * in_stride + b_tile, bytes - b_tile);
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(con
         acc ^= a;
     }
     const rsrc_t ro = make_rsrc(out + b_tile, bytes - b_tile);
-    __builtin_amdgcn_raw_buffer_store_b128(acc, ro, tid * 16, 0, kStreamPolicy);
+    __builtin_amdgcn_raw_buffer_store_b128(acc, ro, tid * 16, 0, kStreamStorePolicy);
 }
 
 template <int NSRC>

@@ -81,9 +81,17 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef __attribute__((address_space(3))) void lds_void;
 
 // Cache policy of the bulk streams (codes, binary16 values): every byte is
-// touched exactly once, so they are marked non-temporal, which measurably
-// raises streaming bandwidth on this part (about +10 % for 4 reads : 1 write).
-constexpr int kStreamPolicy = 2;      // "nt" bit of the buffer instruction
+// touched exactly once.  Loads are marked non-temporal (+17 % on a bare 4 reads :
+// 1 write stream against the default policy).  Stores are non-temporal with device
+// scope: the scope bit makes them write through the XCD's L2 as they are issued,
+// which is worth 2-5 % to the one-in / one-out codec kernels.  The non-temporal bit
+// has to stay on the stores: without it a bare 4-in / 1-out stream gains 6 %, but as
+// soon as a kernel also makes the small default-policy loads of scales and
+// zero-points those loads stall (same HBM traffic by the counters, yet the fused
+// kernel goes from 30.4 to 36.4 us and a bare stream with such loads added from
+// 28.6 to 31.7 us).
+constexpr int kStreamLoadPolicy = 2;       // "nt" bit of the buffer instruction
+constexpr int kStreamStorePolicy = 2 | 16; // "nt" and "sc1" bits
 
 __device__ __forceinline__ rsrc_t make_rsrc(const void *base, int64_t bytes_left)
 {
@@ -153,26 +161,41 @@ __device__ __forceinline__ void pin_values(float (&v)[N])
 }
 
 // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (round
-// robin over the 8 XCDs of the part); when the grid is a multiple of 8 the tiles
-// are dealt so that each XCD works through one contiguous eighth of the volume,
-// which streams measurably faster for the many-streams-in, one-stream-out
-// pattern of the fused kernel than interleaving the XCDs tile by tile (the
-// one-in, one-out codec kernels gain nothing from it and keep the plain order).
+// robin over the 8 XCDs of the part).  Tiles are dealt in chunks: the i-th
+// workgroup of XCD x takes tile ((i / CH) * 8 + x) * CH + i % CH, so each XCD
+// streams runs of CH consecutive tiles (512 KB of every source) and the eight
+// XCDs together advance through one window of 8 * CH tiles.  Measured on a bare
+// 4-in / 1-out stream of the headline size: tile-by-tile interleaving of the XCDs
+// 28.5 us, one contiguous eighth of the volume per XCD 25.8 us, chunks of 16 / 64 /
+// 256 / 1024 tiles 25.7 / 25.5 / 25.1 / 25.6 us (fused kernels: 2-3 % where HBM
+// bounds them).  Tiles beyond the last whole window keep the plain order; volumes
+// smaller than a window use a smaller power-of-two chunk.
 // n = number of workgroups of the launch.  The callers derive it from the volume instead of reading
 // gridDim: the explicit kernel arguments are preloaded into scalar registers at wavefront start (see
 // the build flags) while gridDim would cost a memory read before the first load can be issued, and
 // these short-lived wavefronts are sensitive to that delay (1 % of the fused kernel's time).
+template <int CH>
 __device__ __forceinline__ u32 xcd_tile(u32 n)
 {
+    static_assert(CH > 0 && (CH & (CH - 1)) == 0, "chunk length is a power of two");
     const u32 b = blockIdx.x;
-    return (n & 7u) == 0 ? (b & 7u) * (n >> 3) + (b >> 3) : b;
+    if (n < 16u) return b;
+    const u32 per_xcd = n >> 3;
+    constexpr u32 kLogCh = (u32)__builtin_ctz((unsigned)CH);
+    const u32 sh = per_xcd >= (u32)CH ? kLogCh : (u32)(31 - __builtin_clz(per_xcd));   // log2 of the chunk length
+    const u32 window = 8u << sh;
+    if (b >= (n & ~(window - 1u))) return b;
+    const u32 x = b & 7u, i = b >> 3;
+    return ((((i >> sh) << 3) + x) << sh) + (i & ((1u << sh) - 1u));
 }
+// chunk length for a tile of `tile_code_bytes` of every source: 512 KB runs
+constexpr int xcd_chunk(int tile_code_bytes) { return (512 * 1024) / tile_code_bytes; }
 
 // One coalesced 1 KB piece of a wavefront: lane l's 16 bytes at `off` (which
 // already contains 16*l) go to lds_piece + 16*l.
 __device__ __forceinline__ void dma_piece(rsrc_t r, u32 off, void *lds_piece)
 {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds_piece, 16, off, 0, 0, kStreamPolicy);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds_piece, 16, off, 0, 0, kStreamLoadPolicy);
 }
 
 // ---------------------------------------------------------------------------
@@ -649,10 +672,10 @@ __device__ __forceinline__ void store_codes(const u32 *word, rsrc_t r, u32 wave,
     const u32 wave_off = wave * (64 * OUT_BYTES);
     if constexpr (OUT_BYTES == 8) {
         __builtin_amdgcn_raw_buffer_store_b64(u32x2{word[0], word[1]}, r, wave_off + lane * 8, 0,
-                                              kStreamPolicy);
+                                              kStreamStorePolicy);
     } else if constexpr (OUT_BYTES == 16) {
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, r,
-                                               wave_off + lane * 16, 0, kStreamPolicy);
+                                               wave_off + lane * 16, 0, kStreamStorePolicy);
     } else {
         static_assert(OUT_BYTES == 32, "8, 16 or 32 code bytes per lane");
         u32x4 *mine = reinterpret_cast<u32x4 *>(img + lane * 32);
@@ -661,7 +684,7 @@ __device__ __forceinline__ void store_codes(const u32 *word, rsrc_t r, u32 wave,
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const u32x4 a = *reinterpret_cast<const u32x4 *>(img + k * 1024 + lane * 16);
-            __builtin_amdgcn_raw_buffer_store_b128(a, r, wave_off + k * 1024 + lane * 16, 0, kStreamPolicy);
+            __builtin_amdgcn_raw_buffer_store_b128(a, r, wave_off + k * 1024 + lane * 16, 0, kStreamStorePolicy);
         }
     }
 }
@@ -935,7 +958,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     const int gw_shift = __builtin_ctz(gw);
     const int entries = NSRC * gw;
 
-    const u32 tile = xcd_tile((u32)((n_elems + kTileElems - 1) / kTileElems));
+    const u32 tile = xcd_tile<xcd_chunk(BT * 16)>((u32)((n_elems + kTileElems - 1) / kTileElems));
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
 
@@ -946,6 +969,12 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     // 14 % once a group spans 8 lanes or more, while the per-lane conversions cost the narrow-group
     // kernels 1.5 %.
     constexpr bool kDirectMeta = (LPG == 0 || LPG >= 8);
+    // the code load of source j, straight into its landing slot
+    auto issue_source = [&](int j) {
+        const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
+                                    (n_elems - e_tile) * BITS_IN / 8);
+        dma_piece(rc, tid * 16, &landing[wave][j][0]);
+    };
     bool all_fast;
     MetaRec mrec[kDirectMeta ? NSRC : 1];
     const MetaRec *my_meta = nullptr;
@@ -961,11 +990,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
         }
         issue_order_fence();
 #pragma unroll
-        for (int j = 0; j < NSRC; ++j) {
-            const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
-                                        (n_elems - e_tile) * BITS_IN / 8);
-            dma_piece(rc, tid * 16, &landing[wave][j][0]);
-        }
+        for (int j = 0; j < NSRC; ++j) issue_source(j);
         issue_order_fence();
         if constexpr (HM) {
 #pragma unroll
@@ -1000,11 +1025,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
 
         // --- codes: straight into the landing zone
 #pragma unroll
-        for (int j = 0; j < NSRC; ++j) {
-            const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
-                                        (n_elems - e_tile) * BITS_IN / 8);
-            dma_piece(rc, tid * 16, &landing[wave][j][0]);
-        }
+        for (int j = 0; j < NSRC; ++j) issue_source(j);
         issue_order_fence();
 
         // --- table: check, convert, publish
@@ -1103,7 +1124,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
     const int lpg_v = LPG > 0 ? LPG : lpg;
-    const u32 tile = xcd_tile((u32)((n_elems + kTileElems - 1) / kTileElems));
+    const u32 tile = xcd_tile<xcd_chunk(BT * 16)>((u32)((n_elems + kTileElems - 1) / kTileElems));
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
     const u32 gi = (tid * EPL) >> group_shift;
@@ -1114,12 +1135,13 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) sc[j] = scales_in[(int64_t)j * meta_stride + g_lane];
     issue_order_fence();
-#pragma unroll
-    for (int j = 0; j < NSRC; ++j) {
+    auto issue_source = [&](int j) {
         const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
                                     (n_elems - e_tile) * BITS_IN / 8);
         dma_piece(rc, tid * 16, &landing[wave][j][0]);
-    }
+    };
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) issue_source(j);
     issue_order_fence();
 
     const ZeroConst zc = sym_zero_const<BITS_IN>();
@@ -1185,7 +1207,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequantize(
 
     const float s_raw = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, gi * 4, 0, 0));
     float s = s_raw;
-    const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamPolicy);
+    const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, tid * 16, 0, kStreamLoadPolicy);
 
     float d[EPL];
     if constexpr (CODEC == kFp8) {
@@ -1226,7 +1248,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequantize(
     for (int k = 0; k < kPieces; ++k) {
         const u32x4 o = *reinterpret_cast<const u32x4 *>(&img[wave][k * 1024 + lane * 16]);
         __builtin_amdgcn_raw_buffer_store_b128(o, ry, wave * (kPieces * 1024) + k * 1024 + lane * 16, 0,
-                                               kStreamPolicy);
+                                               kStreamStorePolicy);
     }
 }
 

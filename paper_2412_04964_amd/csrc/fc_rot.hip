@@ -211,7 +211,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
             pack_lane<BITS, EPL>(v[p], inv * fwd, zf, mx[p], word);
         }
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, rc,
-                                               (p * T + tid) * 16, 0, kStreamPolicy);
+                                               (p * T + tid) * 16, 0, kStreamStorePolicy);
         const u32 lane_in_row = p * T + tid;
         if ((lane_in_row & (u32)(lpg - 1)) == 0) {
             const int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
@@ -245,7 +245,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
         const u32 lane_in_row = p * T + tid;
         const int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
         const float s = scales[gi];
-        const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, lane_in_row * 16, 0, kStreamPolicy);
+        const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, lane_in_row * 16, 0, kStreamLoadPolicy);
         float d[EPL];
         if constexpr (CODEC == kFp8) {
             const u32 w[4] = {a[0], a[1], a[2], a[3]};
@@ -288,7 +288,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
         for (int k = 0; k < kPieces; ++k) {
             const u32x4 o = *reinterpret_cast<const u32x4 *>(&img[wave][k * 1024 + lane * 16]);
             __builtin_amdgcn_raw_buffer_store_b128(o, ry, (p * T * EPL + wave * 64 * EPL) * 2 + k * 1024 + lane * 16,
-                                                   0, kStreamPolicy);
+                                                   0, kStreamStorePolicy);
         }
     }
 }

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_quantize_wide(
         else
             pack_lane<BITS, EPL>(v[p], inv, zf, mx, word);
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, rc,
-                                               (p * blockDim.x + tid) * 16, 0, kStreamPolicy);
+                                               (p * blockDim.x + tid) * 16, 0, kStreamStorePolicy);
     }
     if (tid == 0) {
         scales[blockIdx.x] = CODEC == kAsymH ? __builtin_bit_cast(float, pack_meta(s, zf)) : s;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_dequant_reduce_requant_wide(
 #pragma unroll
                 for (int p = 0; p < P; ++p)
                     dst[d][p] = __builtin_amdgcn_raw_buffer_load_b128(r, (p * blockDim.x + tid) * 16, 0,
-                                                                      kStreamPolicy);
+                                                                      kStreamLoadPolicy);
             }
     };
     auto fold_chunk = [&](int j0, const u32x4 (&src)[D][P]) {
