@@ -55,19 +55,35 @@ def dequantize_bytes(w) -> int:
     return m * w.bits_out // 8 + w.meta_bytes_per_group * m // w.group + 2 * m
 
 
-def load_traffic(name):
-    """HBM bytes per fused launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the
-    committed, calibrated summary under profiles/); None when no measurement exists."""
+def load_profile_constant(name, key):
+    """A per-launch figure of the fused kernel from the committed, calibrated rocprofv3 counter summary under
+    profiles/ (hardware counters cannot be read from inside this process): `fused_hbm_bytes_per_launch` from
+    --pmc FETCH_SIZE / WRITE_SIZE, `fused_valu_wave_instructions_per_launch` from --pmc SQ_INSTS_VALU.  None
+    when no measurement exists.  These are stored constants, not measurements of the run that prints them."""
     p = os.path.join(ROOT, "profiles", "traffic_%s.txt" % name)
     if not os.path.exists(p):
         return None
     for line in open(p):
-        if line.startswith("fused_hbm_bytes_per_launch"):
+        if line.startswith(key):
             try:
                 return int(line.split("=")[1])
             except ValueError:
                 return None
     return None
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+# VALU issue peak of the part: 256 compute units x 4 SIMDs, one wave64 instruction per SIMD every 4 cycles at 2.4 GHz
+VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
 
 
 def cpu_baseline(w, x_host, budget_s=20.0):
@@ -119,6 +135,7 @@ def cpu_baseline(w, x_host, budget_s=20.0):
         "value": round(fused_bytes(w) * frac / best / 1e9, 4),
         "unit": "GB/s",
         "cores": 1,
+        "cpu_model": cpu_model(),
         "kind": "oracle",
         "sample": "fused step of the plain-C oracle on rows [0,%d) of %d of volume 0, best of 2, "
                   "%.2f s per run" % (rows, w.tokens, best),
@@ -311,6 +328,25 @@ def main():
     sr_s = sr0.elapsed_time(sr1) * 1e-3 / (sr_reps * B)
     sr_bytes = (N + 1) * slab
 
+    # the opposite cut: the fused kernel's whole instruction stream with its traffic confined to the L2
+    # (fc_fused_compute_probe of the bench library; instantiated for the three asymmetric benchmark configurations)
+    probe_s = None
+    if (w.quantizer == "asym" and not w.rotate and
+            (N, w.bits_in, w.bits_out, g) in ((4, 4, 4, 128), (4, 8, 8, 128), (8, 4, 4, 64)) and T * H >= 64 * 128 * 32):
+        PC = torch.empty_like(C2[0]); PS = torch.empty_like(S2[0]); PZ = torch.empty_like(Z2[0])
+        for _ in range(20):
+            fc.fused_compute_probe(C1[0], S1[0], Z1[0], H, g, w.bits_in, w.bits_out, out=(PC, PS, PZ))
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p_reps = max(10, min(a.steps * B, 500))
+        torch.cuda.synchronize()
+        p0.record()
+        for _ in range(p_reps):
+            fc.fused_compute_probe(C1[0], S1[0], Z1[0], H, g, w.bits_in, w.bits_out, out=(PC, PS, PZ))
+        p1.record()
+        torch.cuda.synchronize()
+        probe_s = p0.elapsed_time(p1) * 1e-3 / p_reps
+        del PC, PS, PZ
+
     # one volume kept hot: the fused launch repeated on a single buffer set, whose working set (inputs and
     # outputs of one launch) fits the 256 MB memory-side cache for every workload but the 8-way fan-in
     cw0, cw1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -342,7 +378,7 @@ def main():
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": a.steps,
-        "warmup": a.warmup,
+        "warmup": settle_steps + max(1, a.warmup),          # untimed steps actually run (config.warmup_requested as passed)
         "ms_per_step": round(wall / a.steps * 1e3, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -359,6 +395,7 @@ def main():
                         + (", Hadamard rotation fused into quantize / dequantize" if w.rotate else ""),
             "n_src": N, "tokens": T, "hidden": H, "group": g, "bits_in": w.bits_in, "bits_out": w.bits_out,
             "volumes_per_step": B,
+            "warmup_requested": a.warmup,
             "settle_steps": settle_steps,
             "stage_order": "volume-major (dependent)" if a.dependent else "stage-major over the batch",
             "launch": "HIP graph replay per stage" if graphs else "eager",
@@ -391,7 +428,9 @@ def main():
                 "us_per_launch": round(cw_s * 1e6, 2),
                 "GBps": round(fused_bytes(w) / cw_s / 1e9, 1),
             },
-            "traffic": load_traffic(w.name),
+            "traffic": load_profile_constant(w.name, "fused_hbm_bytes_per_launch"),
+            "traffic_source": "stored constant: profiles/traffic_%s.txt (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, calibrated "
+                              "against a copy of known size); not measured by this run" % w.name,
             "stream_reference": {
                 "what": "fc_stream_reference: %d code slabs in, 1 out, the fused kernel's tiling and staging, "
                         "no arithmetic, no scales / zero-points" % N,
@@ -402,6 +441,24 @@ def main():
             },
         },
     }
+    if probe_s is not None:
+        valu = load_profile_constant(w.name, "fused_valu_wave_instructions_per_launch")
+        out["roofline"]["compute_only"] = {
+            "what": "fc_fused_compute_probe: the same launch (grid, instructions per wavefront) with every workgroup "
+                    "working in the first 64 tiles, which stay in the L2: what the arithmetic alone costs",
+            "us_per_launch": round(probe_s * 1e6, 2),
+            "fused_over_compute_only": round(fused_s / probe_s, 4),
+        }
+        if valu:
+            rate = valu / fused_s
+            out["roofline"]["alu"] = {
+                "bound": "alu", "unit": "wave64 VALU instructions/s",
+                "instructions_per_launch": valu,
+                "instructions_source": "stored constant: profiles/traffic_%s.txt (rocprofv3 --pmc SQ_INSTS_VALU)" % w.name,
+                "achieved": round(rate, 1), "peak": VALU_PEAK_WAVE_INSTR_PER_S,
+                "frac": round(rate / VALU_PEAK_WAVE_INSTR_PER_S, 4),
+                "what": "peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per wave64 instruction",
+            }
     # the paper's own figures: other hardware (L40, A100) and other quantities (end-to-end all-reduce latency
     # against NCCL, time to first token), quoted as context only, never as a baseline for `value`
     out["paper_context"] = ("Flash Communication reports up to 3.18x lower all-reduce latency than NCCL's ring "

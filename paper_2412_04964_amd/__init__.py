@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     allreduce_sim_rot,
     allreduce_sim_static,
     bench_lib,
+    fused_compute_probe,
     dequantize_rot,
     quantize_rot,
     stream_reference,
@@ -44,7 +45,7 @@ from .binding import (  # noqa: F401
 
 __all__ = [
     "QUANTIZER_ASYM", "QUANTIZER_FP8", "QUANTIZER_SYM", "allreduce_sim_rot", "dequantize_rot", "quantize_rot",
-    "stream_reference", "allreduce_sim_static", "STATIC_SCRATCH_BYTES", "bench_lib",
+    "stream_reference", "allreduce_sim_static", "STATIC_SCRATCH_BYTES", "bench_lib", "fused_compute_probe",
     "FcError", "allreduce_sim", "allreduce_sim_fp8", "allreduce_sim_sym", "allreduce_sim_workspace_bytes",
     "dequant_reduce_requant", "dequant_reduce_requant_fp8", "dequant_reduce_requant_sym", "dequantize",
     "dequantize_fp8", "dequantize_sym", "last_hip_error", "lib", "lib_path", "quantize", "quantize_fp8",

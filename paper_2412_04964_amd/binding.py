@@ -489,6 +489,9 @@ def bench_lib() -> ctypes.CDLL:
         L.fc_stream_reference.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p]
         L.fc_stream_reference.restype = ctypes.c_int
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        L.fc_fused_compute_probe.argtypes = [vp, i64, vp, vp, i64, i32, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.fc_fused_compute_probe.restype = i32
         _bench_lib = L
     return _bench_lib
 
@@ -504,3 +507,16 @@ def stream_reference(src, out):
     _check(bench_lib().fc_stream_reference(src.data_ptr(), src.stride(0) if n > 1 else 0, n, nbytes, out.data_ptr(),
                                            _stream()), "fc_stream_reference")
     return out
+
+
+def fused_compute_probe(codes_in, scales_in, zeros_in, hidden: int, group: int, bits_in: int, bits_out: int, out):
+    """fc_fused_compute_probe: the launch of dequant_reduce_requant with its memory traffic confined to the L2
+    (benchmark configurations only); `out` as for dequant_reduce_requant, contents meaningless afterwards."""
+    _geometry("fc_fused_compute_probe", hidden, group, bits_in, bits_out)
+    n, t, cstride, mstride = _stacked_inputs(codes_in, (scales_in, zeros_in), hidden, group, bits_in,
+                                             [_f32("scales_in"), _f32("zeros_in")])
+    codes, scales, zeros = _coded_outputs(codes_in.device, t, hidden, group, bits_out, out,
+                                          [_f32("scales"), _f32("zeros")])
+    _check(bench_lib().fc_fused_compute_probe(
+        codes_in.data_ptr(), cstride, scales_in.data_ptr(), zeros_in.data_ptr(), mstride, n, t, hidden, group,
+        bits_in, bits_out, codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), _stream()), "fc_fused_compute_probe")

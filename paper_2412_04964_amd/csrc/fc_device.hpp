@@ -49,11 +49,11 @@ constexpr bool is_asym(int codec) { return codec == kAsym || codec == kAsymH; }
 constexpr int lane_elems(int bits) { return 128 / bits; }
 constexpr int block_elems(int bits) { return kBlockThreads * lane_elems(bits); }
 
-// The fused kernel runs 128-thread workgroups when a group fits in 8 lanes (the compile-time
-// LPG instantiations): finer workgroups stream measurably faster (about 2 % on a bare 4-in/1-out
-// copy, up to 3 % on the 8-bit fused kernel).  The run-time-LPG instantiation keeps 256 threads,
-// the span over which it can reduce a group across wavefronts.
-constexpr int fused_block_threads(int lpg) { return lpg > 0 ? 128 : kBlockThreads; }
+// The fused kernel runs 128-thread workgroups for groups of up to 128 lanes (128 lanes = both
+// wavefronts of the workgroup): finer workgroups stream measurably faster (about 2 % on a bare
+// 4-in/1-out copy, up to 3 % on the 8-bit fused kernel).  256-lane groups need 256 threads, the span
+// over which the kernel reduces a group across wavefronts.
+constexpr int fused_block_threads(int lpg) { return (lpg > 0 && lpg <= 128) ? 128 : kBlockThreads; }
 // Launch-bound volumes (at most one wavefront per compute unit of the part): the asymmetric g = 128 instantiations
 // also exist with single-wavefront workgroups, which spreads the work over twice as many compute units and turns the
 // wavefront index into a constant (decode shape: 3.46 -> 3.30 us per launch).
@@ -923,52 +923,57 @@ __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
 // keeps 8 wavefronts resident per SIMD.  Each source is read back with one
 // ds_read_b128 per lane (conflict-free) as soon as its load has retired.
 // The group scales / zero-points reach the lanes in one of two ways, chosen at
-// compile time by the group width (see kDirectMeta below).
+// compile time by the group width (see kEntryMeta below).
 // HM = true: binary16 metadata; scales_in / scales_out are the arrays of 32-bit
 // metadata words and the zeros arrays are not used.
 // BT: threads per workgroup.  Besides the default, the launcher uses single-wavefront workgroups (BT = 64, narrow
 // groups only) for volumes too small to give every compute unit a wavefront.
-template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool HM = false, int BT = fused_block_threads(LPG)>
+// WRAP: 0 in the library.  The benchmark aid instantiates WRAP > 0, which makes every workgroup work on tile
+// (its tile % WRAP): the instruction stream of a full launch with its memory traffic confined to a few tiles that
+// stay in the L2, i.e. the time the kernel's arithmetic takes when HBM is out of the picture.
+template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool HM = false, int BT = fused_block_threads(LPG),
+          int WRAP = 0>
 __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, const float *__restrict__ zeros_in, int64_t meta_stride,
-    int64_t n_elems, int lpg, int group_shift,
+    int64_t n_elems, int group_shift,
     uint8_t *__restrict__ codes_out, float *__restrict__ scales_out, float *__restrict__ zeros_out)
 {
     constexpr int EPL = lane_elems(BITS_IN);
     constexpr int kWaveElems = 64 * EPL;
     constexpr int kWaves = BT / 64;
-    static_assert(BT == fused_block_threads(LPG) || (BT == 64 && LPG > 0), "unsupported workgroup size");
+    static_assert(BT == fused_block_threads(LPG) || (BT == 64 && LPG <= 64), "unsupported workgroup size");
     constexpr int kTileElems = BT * EPL;
     constexpr int kOutBytes = EPL * BITS_OUT / 8;             // code bytes a lane writes: 8, 16 or 32
-    constexpr int kMaxGw = LPG > 0 ? 64 / LPG : 8;            // groups per wavefront tile (upper bound)
-    constexpr int K = (NSRC * kMaxGw + 63) / 64;              // table entries per lane
+    static_assert(LPG >= 1 && LPG <= 256 && (LPG & (LPG - 1)) == 0, "lanes per group: a power of two up to 256");
+    constexpr int gw = LPG >= 64 ? 1 : 64 / LPG;              // groups per wavefront tile
+    constexpr int gw_shift = __builtin_ctz((unsigned)gw);
+    constexpr int entries = NSRC * gw;
+    constexpr bool kSpansWaves = LPG > 64;                    // a group takes more than one wavefront
+    constexpr int K = (entries + 63) / 64;                    // table entries per lane
     struct MetaRec { float s; u32 z; };                       // z: packed halves (fast) or fp32 bits
 
     __shared__ __attribute__((aligned(16))) uint8_t landing[kWaves][NSRC][1024];
-    __shared__ MetaRec meta[(LPG == 0 || LPG >= 8) ? 1 : kWaves][NSRC * kMaxGw];
-    __shared__ float slot[LPG == 0 ? kWaves : 1][2];     // cross-wavefront min / max (wide groups)
+    __shared__ MetaRec meta[LPG >= 8 ? 1 : kWaves][LPG >= 8 ? 1 : entries];
+    __shared__ float slot[kSpansWaves ? kWaves : 1][2];       // cross-wavefront min / max (wide groups)
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
-    const int lpg_v = LPG > 0 ? LPG : lpg;
-    const int gw = lpg_v < 64 ? 64 / lpg_v : 1;               // groups per wavefront tile
-    const int gw_shift = __builtin_ctz(gw);
-    const int entries = NSRC * gw;
 
-    const u32 tile = xcd_tile<xcd_chunk(BT * 16)>((u32)((n_elems + kTileElems - 1) / kTileElems));
+    u32 tile = xcd_tile<xcd_chunk(BT * 16)>((u32)((n_elems + kTileElems - 1) / kTileElems));
+    if constexpr (WRAP > 0) tile %= (u32)WRAP;
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
 
-    // Scales and zero-points of the sources.  Narrow groups (up to 4 lanes): the NSRC x (64/LPG)
-    // pairs of the wavefront tile are loaded one per lane, checked and converted once, and handed to
-    // the consuming lanes through an LDS table.  Wider groups: every lane loads the pairs of its own
-    // group (few distinct addresses per wavefront); measured, the table costs the 4-bit kernel up to
-    // 14 % once a group spans 8 lanes or more, while the per-lane conversions cost the narrow-group
-    // kernels 1.5 %.
-    constexpr bool kDirectMeta = (LPG == 0 || LPG >= 8);
+    // Scales and zero-points of the sources: the NSRC x (groups of the wavefront tile) pairs are loaded one per
+    // lane, checked and converted once, and handed to the lanes of each group.  Narrow groups (up to 4 lanes: 16 or
+    // more groups per wavefront tile, possibly several entries per lane) go through an LDS table; wider groups
+    // (at most 8 groups per tile, so at most 64 entries: one per lane) are handed over with ds_bpermute, which
+    // needs no table and no address arithmetic (0.2-0.7 us per launch at the headline shape against every lane
+    // loading and converting the pairs of its own group; the LDS table measured up to 14 % slower there).
+    constexpr bool kEntryMeta = LPG >= 8;
     // the code load of source j, straight into its landing slot
     auto issue_source = [&](int j) {
         const rsrc_t rc = make_rsrc(codes_in + (int64_t)j * codes_stride + e_tile * BITS_IN / 8,
@@ -976,34 +981,30 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
         dma_piece(rc, tid * 16, &landing[wave][j][0]);
     };
     bool all_fast;
-    MetaRec mrec[kDirectMeta ? NSRC : 1];
+    MetaRec mrec[kEntryMeta ? NSRC : 1];
     const MetaRec *my_meta = nullptr;
-    if constexpr (kDirectMeta) {
-        const u32 gi_lane = (tid * EPL) >> group_shift;
-        int64_t g_lane = g_tile + gi_lane;
-        g_lane = g_lane < n_groups ? g_lane : n_groups - 1;   // ragged tail: stay inside the array
-        float ms_[NSRC], mz_[NSRC];
-#pragma unroll
-        for (int j = 0; j < NSRC; ++j) {
-            ms_[j] = scales_in[(int64_t)j * meta_stride + g_lane];
-            if constexpr (!HM) mz_[j] = zeros_in[(int64_t)j * meta_stride + g_lane];
-        }
+    if constexpr (kEntryMeta) {
+        // one lane per (source, group of the wavefront tile): entry e = j * gw + g
+        static_assert(entries <= 64, "one entry per lane");
+        const u32 e = lane < (u32)entries ? lane : 0u;            // surplus lanes repeat entry 0
+        int64_t gi = ((e_tile + (int64_t)wave * kWaveElems) >> group_shift) + (e & (u32)(gw - 1));
+        gi = gi < n_groups ? gi : n_groups - 1;                   // ragged tail: stay inside the array
+        const int64_t at = (int64_t)(e >> gw_shift) * meta_stride + gi;
+        float es = scales_in[at], ez;
+        if constexpr (!HM) ez = zeros_in[at];
         issue_order_fence();
 #pragma unroll
         for (int j = 0; j < NSRC; ++j) issue_source(j);
         issue_order_fence();
-        if constexpr (HM) {
-#pragma unroll
-            for (int j = 0; j < NSRC; ++j) unpack_meta(__builtin_bit_cast(u32, ms_[j]), ms_[j], mz_[j]);
-        }
-        bool ok = true;
-#pragma unroll
-        for (int j = 0; j < NSRC; ++j) ok = ok && zero_is_fast(mz_[j]);
-        all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
+        if constexpr (HM) unpack_meta(__builtin_bit_cast(u32, es), es, ez);
+        all_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(ez)) == 0;
+        const u32 ezc = all_fast ? pack_zero_const(ez) : __builtin_bit_cast(u32, ez);
+        const u32 mine = ((LPG >= 64 ? 0u : lane / (u32)LPG)) * 4u;   // byte index of entry (0, my group)
 #pragma unroll
         for (int j = 0; j < NSRC; ++j) {
-            mrec[j].s = ms_[j];
-            mrec[j].z = all_fast ? pack_zero_const(mz_[j]) : __builtin_bit_cast(u32, mz_[j]);
+            const int from = (int)mine + j * gw * 4;
+            mrec[j].s = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, __builtin_bit_cast(int, es)));
+            mrec[j].z = (u32)__builtin_amdgcn_ds_bpermute(from, (int)ezc);
         }
     } else {
         // --- table loads (small, first: vector-memory results return in issue order).
@@ -1047,7 +1048,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
                 meta[wave][idx] = r;
             }
         }
-        my_meta = &meta[wave][lane / (u32)lpg_v];
+        my_meta = &meta[wave][lane / (u32)LPG];
     }
 
     float acc[EPL];
@@ -1063,7 +1064,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
             wait_vmem_outstanding(NSRC - 1 - j);
             u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
             MetaRec r;
-            if constexpr (kDirectMeta)
+            if constexpr (kEntryMeta)
                 r = mrec[j];
             else
                 r = my_meta[j * gw];
@@ -1084,15 +1085,15 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     // --- requantize the sums and store
     u32 word[EPL * BITS_OUT / 32];
     float s, zf;
-    if constexpr (LPG == 0)
-        quantize_lane_any<BITS_OUT, EPL, HM>(acc, lpg, slot, wave, lane, word, s, zf);
+    if constexpr (kSpansWaves)
+        quantize_lane_any<BITS_OUT, EPL, HM>(acc, LPG, slot, wave, lane, word, s, zf);
     else
-        quantize_lane<BITS_OUT, EPL, LPG, HM>(acc, lpg, word, s, zf);
+        quantize_lane<BITS_OUT, EPL, LPG, HM>(acc, LPG, word, s, zf);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
     const rsrc_t rz = make_rsrc(HM ? scales_out + g_tile : zeros_out + g_tile, (n_groups - g_tile) * 4);
     store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
-    if ((tid & (lpg_v - 1)) == 0) {
+    if ((tid & (LPG - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
         store_f32(rs, gi * 4, HM ? __builtin_bit_cast(float, pack_meta(s, zf)) : s);
         if constexpr (!HM) store_f32(rz, gi * 4, zf);
@@ -1109,7 +1110,7 @@ template <int BITS_IN, int BITS_OUT, int NSRC, int LPG, bool FP8 = false>
 __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_requant_sym(
     const uint8_t *__restrict__ codes_in, int64_t codes_stride,
     const float *__restrict__ scales_in, int64_t meta_stride,
-    int64_t n_elems, int lpg, int group_shift,
+    int64_t n_elems, int group_shift,
     uint8_t *__restrict__ codes_out, float *__restrict__ scales_out)
 {
     constexpr int EPL = lane_elems(BITS_IN);
@@ -1119,11 +1120,12 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     __shared__ __attribute__((aligned(16))) uint8_t landing[kWaves][NSRC][1024];
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
-    __shared__ float slot[LPG == 0 ? kWaves : 1][2];     // cross-wavefront maximum (wide groups)
+    static_assert(LPG >= 1 && LPG <= 256 && (LPG & (LPG - 1)) == 0, "lanes per group: a power of two up to 256");
+    constexpr bool kSpansWaves = LPG > 64;
+    __shared__ float slot[kSpansWaves ? kWaves : 1][2];       // cross-wavefront maximum (wide groups)
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t n_groups = n_elems >> group_shift;
-    const int lpg_v = LPG > 0 ? LPG : lpg;
     const u32 tile = xcd_tile<xcd_chunk(BT * 16)>((u32)((n_elems + kTileElems - 1) / kTileElems));
     const int64_t e_tile = (int64_t)tile * kTileElems;
     const int64_t g_tile = e_tile >> group_shift;
@@ -1168,18 +1170,18 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     float s;
     if constexpr (FP8) {
         static_assert(!FP8 || (BITS_IN == 8 && BITS_OUT == 8), "E4M3 is an 8-bit code");
-        if constexpr (LPG == 0)
-            quantize_lane_fp8_any<EPL>(acc, lpg, slot, wave, lane, word, s);
+        if constexpr (kSpansWaves)
+            quantize_lane_fp8_any<EPL>(acc, LPG, slot, wave, lane, word, s);
         else
-            quantize_lane_fp8<EPL, LPG>(acc, lpg, word, s);
-    } else if constexpr (LPG == 0)
-        quantize_lane_sym_any<BITS_OUT, EPL>(acc, lpg, slot, wave, lane, word, s);
+            quantize_lane_fp8<EPL, LPG>(acc, LPG, word, s);
+    } else if constexpr (kSpansWaves)
+        quantize_lane_sym_any<BITS_OUT, EPL>(acc, LPG, slot, wave, lane, word, s);
     else
-        quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, lpg, word, s);
+        quantize_lane_sym<BITS_OUT, EPL, LPG>(acc, LPG, word, s);
     const rsrc_t rc = make_rsrc(codes_out + e_tile * BITS_OUT / 8, (n_elems - e_tile) * BITS_OUT / 8);
     const rsrc_t rs = make_rsrc(scales_out + g_tile, (n_groups - g_tile) * 4);
     store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
-    if ((tid & (lpg_v - 1)) == 0) store_f32(rs, gi * 4, s);
+    if ((tid & (LPG - 1)) == 0) store_f32(rs, gi * 4, s);
 }
 
 // Dequantize to binary16 (Algorithm 1, last step): y = half_rne((q - z) * s).

@@ -23,20 +23,20 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
     if (a.codec == CODEC_FP8) {
         return launch_kernel(k_dequant_reduce_requant_sym<8, 8, NSRC, LPG, true>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
-                a.n_elems, a.group / lane_elems(8), log2_int(a.group),
+                a.n_elems, log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
     }
 #endif
     if (a.codec == CODEC_SYM) {
         return launch_kernel(k_dequant_reduce_requant_sym<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.meta_stride,
-                a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                a.n_elems, log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out);
     }
     if (a.codec == CODEC_ASYMH) {
         return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, true>, dim3((unsigned)blocks), dim3(BT), stream,
                 static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, nullptr,
-                a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                a.meta_stride, a.n_elems, log2_int(a.group),
                 static_cast<uint8_t *>(a.codes_out), a.scales_out, nullptr);
     }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
@@ -46,18 +46,18 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
         if (waves <= kSmallLaunchWaves) {
             return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, false, 64>, dim3((unsigned)waves), dim3(64), stream,
                     static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
-                    a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+                    a.meta_stride, a.n_elems, log2_int(a.group),
                     static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
         }
     }
     return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>, dim3((unsigned)blocks), dim3(BT), stream,
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
-            a.meta_stride, a.n_elems, a.group / lane_elems(FC_BITS_IN), log2_int(a.group),
+            a.meta_stride, a.n_elems, log2_int(a.group),
             static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
 }
 
-// groups spanning 1, 2, 4 or 8 lanes get their own instantiation; larger
-// groups share one that reads the lane count at run time
+// one instantiation per group width in lanes: 1 ... 128 lanes in 128-thread workgroups, 256 lanes in
+// 256-thread workgroups (wider groups go to fc_wide.hip before this point)
 template <int NSRC>
 static hipError_t launch_n(const FusedArgs &a, hipStream_t stream)
 {
@@ -66,7 +66,12 @@ static hipError_t launch_n(const FusedArgs &a, hipStream_t stream)
     case 2: return launch_nl<NSRC, 2>(a, stream);
     case 4: return launch_nl<NSRC, 4>(a, stream);
     case 8: return launch_nl<NSRC, 8>(a, stream);
-    default: return launch_nl<NSRC, 0>(a, stream);
+    case 16: return launch_nl<NSRC, 16>(a, stream);
+    case 32: return launch_nl<NSRC, 32>(a, stream);
+    case 64: return launch_nl<NSRC, 64>(a, stream);
+    case 128: return launch_nl<NSRC, 128>(a, stream);
+    case 256: return launch_nl<NSRC, 256>(a, stream);
+    default: return hipErrorInvalidValue;
     }
 }
 
