@@ -31,7 +31,7 @@ __global__ __launch_bounds__(fused_block_threads(1)) void k_stream_reference(con
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) {
         wait_vmem_outstanding(NSRC - 1 - j);
-        u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+        u32x4 a = lds_read_b128_issue(&landing[wave][0][lane * 16], j * 1024);
         lds_read_complete(a);
         acc ^= a;
     }

@@ -127,11 +127,13 @@ __device__ __forceinline__ void wait_vmem_outstanding(int n)
 // by not waiting at all in others; the landing zone is therefore ordered by
 // hand: wait_vmem_outstanding before, lds_read_complete after.)  The value
 // returned must not be used before lds_read_complete(v) has been called.
-__device__ __forceinline__ u32x4 lds_read_b128_issue(const void *p)
+// `byte_off` (a compile-time constant once the caller's loop is unrolled, at most 65535) goes into the
+// instruction's offset field, so one address register serves every landing slot of the wavefront.
+__device__ __forceinline__ u32x4 lds_read_b128_issue(const void *p, int byte_off = 0)
 {
     u32x4 v;
     const u32 addr = (u32)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(byte_off) : "memory");
     return v;
 }
 
@@ -213,6 +215,45 @@ constexpr int kDppQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
 constexpr int kDppRowMirror = 0x140;      // lane i <-> 15-i inside each 16 lanes
 
+// min / max of a value with the same value in the lane that CTRL selects, in ONE instruction (the DPP operand
+// modifier on v_min_f32 / v_max_f32 themselves).  Written as inline assembly because the compiler's own sequence
+// is a DPP move, a canonicalizing v_max x, x and then the min: three instructions.  The instruction is the one
+// fminf / fmaxf end in, so results are unchanged.  "s_nop 1": a DPP read of a register needs two wait states
+// after the vector instruction that wrote it, which the compiler cannot insert for code it does not see.
+template <int CTRL>
+__device__ __forceinline__ float dpp_min(float v)
+{
+    float r;
+    if constexpr (CTRL == kDppQuadXor1)
+        asm("s_nop 1\n\tv_min_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else if constexpr (CTRL == kDppQuadXor2)
+        asm("s_nop 1\n\tv_min_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else if constexpr (CTRL == kDppRowHalfMirror)
+        asm("s_nop 1\n\tv_min_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else {
+        static_assert(CTRL == kDppRowMirror, "unsupported DPP control");
+        asm("s_nop 1\n\tv_min_f32_dpp %0, %1, %1 row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    }
+    return r;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    float r;
+    if constexpr (CTRL == kDppQuadXor1)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else if constexpr (CTRL == kDppQuadXor2)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else if constexpr (CTRL == kDppRowHalfMirror)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    else {
+        static_assert(CTRL == kDppRowMirror, "unsupported DPP control");
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1" : "=v"(r) : "v"(v));
+    }
+    return r;
+}
+
 // All 64 lanes must be active when this is called.  The group spans `lpg`
 // adjacent lanes (a power of two, 1..64); LPG > 0 fixes it at compile time,
 // LPG == 0 reads the run-time value.
@@ -221,20 +262,20 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lpg_rt)
 {
     const int lpg = LPG > 0 ? LPG : lpg_rt;
     if (lpg >= 2) {
-        mn = fminf(mn, dpp_read<kDppQuadXor1>(mn));
-        mx = fmaxf(mx, dpp_read<kDppQuadXor1>(mx));
+        mn = dpp_min<kDppQuadXor1>(mn);
+        mx = dpp_max<kDppQuadXor1>(mx);
     }
     if (lpg >= 4) {
-        mn = fminf(mn, dpp_read<kDppQuadXor2>(mn));
-        mx = fmaxf(mx, dpp_read<kDppQuadXor2>(mx));
+        mn = dpp_min<kDppQuadXor2>(mn);
+        mx = dpp_max<kDppQuadXor2>(mx);
     }
     if (lpg >= 8) {
-        mn = fminf(mn, dpp_read<kDppRowHalfMirror>(mn));
-        mx = fmaxf(mx, dpp_read<kDppRowHalfMirror>(mx));
+        mn = dpp_min<kDppRowHalfMirror>(mn);
+        mx = dpp_max<kDppRowHalfMirror>(mx);
     }
     if (lpg >= 16) {
-        mn = fminf(mn, dpp_read<kDppRowMirror>(mn));
-        mx = fmaxf(mx, dpp_read<kDppRowMirror>(mx));
+        mn = dpp_min<kDppRowMirror>(mn);
+        mx = dpp_max<kDppRowMirror>(mx);
     }
     if (lpg >= 32) {
         mn = fminf(mn, __shfl_xor(mn, 16));
@@ -323,38 +364,37 @@ __device__ __forceinline__ u32 encode(float x, float inv, float zf)
     return (u32)fminf(fmaxf(u, 0.0f), qmax);
 }
 
-// Fast packing of the lane's codes (see quantize_lane): Horner merge of
-// t = rint(x*inv), optionally capped at tmax = qmax - z, plus z on every digit.
+// Fast packing of the lane's codes (see pack_lane): rounding and merging in the integer view of fp32 numbers.
+//   u = x*inv + M with M = 1.5 * 2^23: every fp32 in [2^23, 2^24) is an integer, so this addition rounds x*inv to
+//       an integer with ties to the even one (M is even): u = M + rint(x*inv) exactly, the same t = rint(x*inv)
+//       that v_rndne_f32 gives, and the bit pattern of u is bits(M) + t as a 32-bit integer (t may be negative).
+//   Horner steps h = (h << BITS) + bits(u_i) (one v_lshl_add_u32 per code) merge a whole 32-bit word of codes;
+//       modulo 2^32 the result is bits(M) * 0x11..1 + sum t_i << (BITS * i).
+//   Adding (z - bits(M)) * 0x11..1 once per word leaves sum (t_i + z) << (BITS * i), and every digit t_i + z lies in
+//       [0, 2^BITS - 1] (lower clamp idle, upper clamp applied to u beforehand when CAP), so no carry crosses a digit.
+// z * 0x11..1 = (z * 0x1111) * 0x10001 is formed from the exact fp32 product z * 4369 (|z| < 2048).
 template <int BITS, int EPL, bool CAP>
 __device__ __forceinline__ void pack_codes(const float (&v)[EPL], float inv, float zf, float tmax,
                                            u32 (&word)[EPL * BITS / 32])
 {
-    auto digit = [&](float x) {
-        const float t = rintf(x * inv);
-        return CAP ? fminf(t, tmax) : t;
-    };
-    if constexpr (BITS == 4) {
-        const float zc = zf * 4369.0f;               // z * (1 + 16 + 256 + 4096)
+    constexpr float kMagic = 12582912.0f;
+    constexpr u32 kMagicBits = 0x4B400000u;
+    constexpr int per_word = 32 / BITS;
+    constexpr u32 kOnes = BITS == 4 ? 0x11111111u : 0x01010101u;
+    const float cap = kMagic + tmax;
+    const u32 zc = (u32)(int)(zf * (BITS == 4 ? 4369.0f : 257.0f));      // z * 0x1111 (z * 0x0101)
+    const u32 fix = (zc + (zc << 16)) - kMagicBits * kOnes;
 #pragma unroll
-        for (int w = 0; w < EPL / 8; ++w) {
-            float t[8];
+    for (int w = 0; w < EPL / per_word; ++w) {
+        u32 h = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) t[i] = digit(v[8 * w + i]);
-            const float lo = fmaf(fmaf(fmaf(t[3], 16.0f, t[2]), 16.0f, t[1]), 16.0f, t[0]) + zc;
-            const float hi = fmaf(fmaf(fmaf(t[7], 16.0f, t[6]), 16.0f, t[5]), 16.0f, t[4]) + zc;
-            word[w] = (u32)lo | ((u32)hi << 16);
+        for (int i = per_word - 1; i >= 0; --i) {
+            const float r = v[per_word * w + i] * inv;
+            float u = r + kMagic;
+            if constexpr (CAP) u = fminf(u, cap);
+            h = (h << BITS) + __builtin_bit_cast(u32, u);
         }
-    } else {
-        const float zc = zf * 257.0f;                // z * (1 + 256)
-#pragma unroll
-        for (int w = 0; w < EPL / 4; ++w) {
-            float t[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] = digit(v[4 * w + i]);
-            const float lo = fmaf(t[1], 256.0f, t[0]) + zc;
-            const float hi = fmaf(t[3], 256.0f, t[2]) + zc;
-            word[w] = (u32)lo | ((u32)hi << 16);
-        }
+        word[w] = h + fix;
     }
 }
 
@@ -367,9 +407,7 @@ __device__ __forceinline__ void pack_codes(const float (&v)[EPL], float inv, flo
 // never acts, and since t, z and qmax are small integers the upper clamp can be
 // applied to t: q = min(t, qmax - z) + z exactly; it is skipped altogether when
 // rint(mx*inv), the largest t of the group, does not exceed qmax - z anywhere in
-// the wavefront.  Several codes are then merged in fp32 by Horner steps
-// (t3*16 + t2)*16 + ... , every partial sum an integer below 2^24 and therefore
-// exact, and z*(1 + 16 + 16^2 + 16^3) is added once.
+// the wavefront.  The codes are then rounded and merged as pack_codes describes.
 // Otherwise each code is formed literally as in Eq. 2.
 // `mx` is the group's maximum (the largest t of the group decides whether the
 // upper clamp can act at all); inv and zf come from group_params.
@@ -404,13 +442,18 @@ __device__ __forceinline__ void pack_lane(const float (&v)[EPL], float inv, floa
 template <int EPL>
 __device__ __forceinline__ void lane_minmax(const float (&v)[EPL], float &mn, float &mx)
 {
-    mn = v[0];
-    mx = v[0];
+    // three-input steps throughout (v_min3_f32 / v_max3_f32 take their inputs as they are; the two-input
+    // forms would first be given a canonicalizing instruction per input by the compiler)
+    static_assert(EPL % 2 == 0 && EPL >= 4, "three, then pairs, then the last one");
+    mn = fminf(fminf(v[0], v[1]), v[2]);
+    mx = fmaxf(fmaxf(v[0], v[1]), v[2]);
 #pragma unroll
-    for (int i = 1; i < EPL; ++i) {
-        mn = fminf(mn, v[i]);
-        mx = fmaxf(mx, v[i]);
+    for (int i = 3; i + 1 < EPL; i += 2) {
+        mn = fminf(fminf(mn, v[i]), v[i + 1]);
+        mx = fmaxf(fmaxf(mx, v[i]), v[i + 1]);
     }
+    mn = fminf(mn, v[EPL - 1]);
+    mx = fmaxf(mx, v[EPL - 1]);
 }
 
 template <int BITS, int EPL, int LPG, bool HM = false>
@@ -472,10 +515,10 @@ template <int LPG>
 __device__ __forceinline__ float group_max(float m, int lpg_rt)
 {
     const int lpg = LPG > 0 ? LPG : lpg_rt;
-    if (lpg >= 2) m = fmaxf(m, dpp_read<kDppQuadXor1>(m));
-    if (lpg >= 4) m = fmaxf(m, dpp_read<kDppQuadXor2>(m));
-    if (lpg >= 8) m = fmaxf(m, dpp_read<kDppRowHalfMirror>(m));
-    if (lpg >= 16) m = fmaxf(m, dpp_read<kDppRowMirror>(m));
+    if (lpg >= 2) m = dpp_max<kDppQuadXor1>(m);
+    if (lpg >= 4) m = dpp_max<kDppQuadXor2>(m);
+    if (lpg >= 8) m = dpp_max<kDppRowHalfMirror>(m);
+    if (lpg >= 16) m = dpp_max<kDppRowMirror>(m);
     if (lpg >= 32) m = fmaxf(m, __shfl_xor(m, 16));
     if (lpg >= 64) m = fmaxf(m, __shfl_xor(m, 32));
     return m;
@@ -511,33 +554,29 @@ __device__ __forceinline__ void group_params_sym(float amax, float &s, float &in
 
 // Symmetric FinegrainedQuantize of the lane's EPL values.  |x| <= amax makes
 // |x*inv| <= amax*inv = qm*(1 + O(2^-22)), so |rint(x*inv)| <= qm and neither
-// clamp of Eq. 4 can act.  Digits are merged with the exact fp32 Horner steps
-// of the asymmetric path after a bias of 2^(n-1) per digit, and the bias is
-// removed again by flipping each digit's top bit (offset binary -> two's
-// complement).
+// clamp of Eq. 4 can act.  Digits are rounded and merged as in the asymmetric
+// path (pack_codes) with a bias of 2^(n-1) per digit, and the bias is removed
+// again by flipping each digit's top bit (offset binary -> two's complement).
 template <int BITS, int EPL>
 __device__ __forceinline__ void pack_lane_sym(const float (&v)[EPL], float inv, u32 (&word)[EPL * BITS / 32])
 {
-    if constexpr (BITS == 4) {
+    // as pack_codes with the constant "zero-point" 2^(n-1): offset-binary digits t + 2^(n-1) in [1, 2^n - 1]
+    constexpr float kMagic = 12582912.0f;
+    constexpr u32 kMagicBits = 0x4B400000u;
+    constexpr int per_word = 32 / BITS;
+    constexpr u32 kOnes = BITS == 4 ? 0x11111111u : 0x01010101u;
+    constexpr u32 kTop = BITS == 4 ? 0x88888888u : 0x80808080u;           // 2^(n-1) on every digit
+    constexpr u32 fix = kTop - kMagicBits * kOnes;
 #pragma unroll
-        for (int w = 0; w < EPL / 8; ++w) {
-            float t[8];
+    for (int w = 0; w < EPL / per_word; ++w) {
+        u32 h = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) t[i] = rintf(v[8 * w + i] * inv);
-            const float lo = fmaf(fmaf(fmaf(t[3], 16.0f, t[2]), 16.0f, t[1]), 16.0f, t[0]) + 34952.0f;
-            const float hi = fmaf(fmaf(fmaf(t[7], 16.0f, t[6]), 16.0f, t[5]), 16.0f, t[4]) + 34952.0f;
-            word[w] = ((u32)lo | ((u32)hi << 16)) ^ 0x88888888u;      // 34952 = 8 * 0x1111
+        for (int i = per_word - 1; i >= 0; --i) {
+            const float r = v[per_word * w + i] * inv;
+            const float u = r + kMagic;
+            h = (h << BITS) + __builtin_bit_cast(u32, u);
         }
-    } else {
-#pragma unroll
-        for (int w = 0; w < EPL / 4; ++w) {
-            float t[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] = rintf(v[4 * w + i] * inv);
-            const float lo = fmaf(t[1], 256.0f, t[0]) + 32896.0f;     // 32896 = 128 * 0x0101
-            const float hi = fmaf(t[3], 256.0f, t[2]) + 32896.0f;
-            word[w] = ((u32)lo | ((u32)hi << 16)) ^ 0x80808080u;
-        }
+        word[w] = (h + fix) ^ kTop;
     }
 }
 
@@ -709,6 +748,15 @@ __device__ __forceinline__ void store_f32(rsrc_t r, u32 byte_off, float v)
 __device__ __forceinline__ bool zero_is_fast(float zf)
 {
     return (zf == rintf(zf)) && (zf >= -1700.0f) && (zf <= 1000.0f);
+}
+
+// lanes of the wavefront whose zf fails zero_is_fast, as a mask (the comparisons write lane masks directly;
+// going through a per-lane bool costs two more vector instructions per use)
+__device__ __forceinline__ uint64_t zero_is_slow_mask(float zf)
+{
+    constexpr int kUne = 14, kUlt = 12, kUgt = 10;            // unordered-or: not equal, less, greater
+    return __builtin_amdgcn_fcmpf(zf, rintf(zf), kUne) | __builtin_amdgcn_fcmpf(zf, -1700.0f, kUlt) |
+           __builtin_amdgcn_fcmpf(zf, 1000.0f, kUgt);
 }
 
 // (half(1024 + z), half(64 + z)) packed in one word
@@ -997,7 +1045,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
         for (int j = 0; j < NSRC; ++j) issue_source(j);
         issue_order_fence();
         if constexpr (HM) unpack_meta(__builtin_bit_cast(u32, es), es, ez);
-        all_fast = __builtin_amdgcn_ballot_w64(!zero_is_fast(ez)) == 0;
+        all_fast = zero_is_slow_mask(ez) == 0;
         const u32 ezc = all_fast ? pack_zero_const(ez) : __builtin_bit_cast(u32, ez);
         const u32 mine = ((LPG >= 64 ? 0u : lane / (u32)LPG)) * 4u;   // byte index of entry (0, my group)
 #pragma unroll
@@ -1034,10 +1082,10 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
 #pragma unroll
             for (int it = 0; it < K; ++it) unpack_meta(__builtin_bit_cast(u32, ms[it]), ms[it], mz[it]);
         }
-        bool ok = true;
+        uint64_t slow = 0;
 #pragma unroll
-        for (int it = 0; it < K; ++it) ok = ok && zero_is_fast(mz[it]);
-        all_fast = __builtin_amdgcn_ballot_w64(!ok) == 0;
+        for (int it = 0; it < K; ++it) slow |= zero_is_slow_mask(mz[it]);
+        all_fast = slow == 0;
 #pragma unroll
         for (int it = 0; it < K; ++it) {
             const int idx = it * 64 + (int)lane;
@@ -1062,7 +1110,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
             // source j has landed once no more than the loads of the later
             // sources (issued after it) are outstanding
             wait_vmem_outstanding(NSRC - 1 - j);
-            u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+            u32x4 a = lds_read_b128_issue(&landing[wave][0][lane * 16], j * 1024);
             MetaRec r;
             if constexpr (kEntryMeta)
                 r = mrec[j];
@@ -1153,7 +1201,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
 #pragma unroll
     for (int j = 0; j < NSRC; ++j) {
         wait_vmem_outstanding(NSRC - 1 - j);
-        u32x4 a = lds_read_b128_issue(&landing[wave][j][lane * 16]);
+        u32x4 a = lds_read_b128_issue(&landing[wave][0][lane * 16], j * 1024);
         lds_read_complete(a);
         if constexpr (FP8) {
             const u32 w[4] = {a[0], a[1], a[2], a[3]};
