@@ -26,6 +26,9 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfc.so")
 BENCH_LIB = os.path.join(HERE, "libfc_bench.so")      # measurement aid (include/fc_bench.h), not the product
+# the product library with its fused kernels compiled with -DFC_PLAIN_LANDING_READS (plain, compiler-ordered reads
+# of the landing zones instead of the hand-ordered ones): the GPU tests run the fused cases through both
+PLAIN_LIB = os.path.join(HERE, "libfc_plainreads.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
@@ -47,6 +50,9 @@ for _bi in (4, 8):
                       ["-DFC_BITS_IN=%d" % _bi, "-DFC_BITS_OUT=%d" % _bo]))
 
 
+PLAIN_UNITS = [(src, tag + "_plain", defs + ["-DFC_PLAIN_LANDING_READS"]) for src, tag, defs in UNITS if src == "fc_fused.hip"]
+
+
 def _compile(unit):
     src, tag, defs = unit
     obj = os.path.join(OBJDIR, tag + ".o")
@@ -63,13 +69,15 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(jobs) as ex:
-        results = list(ex.map(_compile, UNITS + BENCH_UNITS))
+        results = list(ex.map(_compile, UNITS + BENCH_UNITS + PLAIN_UNITS))
     if verbose:
         for _, w in results:
             if w:
                 print(w, file=sys.stderr)
     objs = [o for o, _ in results]
-    for lib, members in ((LIB, objs[:len(UNITS)]), (BENCH_LIB, objs[len(UNITS):])):
+    n_u, n_b = len(UNITS), len(BENCH_UNITS)
+    shared = [o for o, (src, _, _) in zip(objs[:n_u], UNITS) if src != "fc_fused.hip"]
+    for lib, members in ((LIB, objs[:n_u]), (BENCH_LIB, objs[n_u:n_u + n_b]), (PLAIN_LIB, shared + objs[n_u + n_b:])):
         tmp = lib + ".tmp.%d" % os.getpid()
         cmd = [HIPCC, "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp, *members]
         r = subprocess.run(cmd, capture_output=True, text=True)

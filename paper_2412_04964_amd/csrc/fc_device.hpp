@@ -99,14 +99,34 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, int64_t bytes_left
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, n, 0x00020000);
 }
 
+// Landing zones: ordering by hand.
+//
+// A buffer-to-LDS load writes LDS when its data arrives, and the compiler does not reliably order LDS reads of
+// that memory after it (in some control-flow shapes it waits for ALL outstanding vector-memory operations, in
+// others for none).  The kernels therefore read a landing zone with an LDS instruction the compiler does not see
+// (lds_read_b128_issue) and fence it themselves:
+//     wait_vmem_outstanding(k);   a = lds_read_b128_issue(zone);   ...   lds_read_complete(a);   use a
+// INVARIANT the callers keep: vector-memory operations of a wavefront complete in issue order, and vmcnt counts ALL
+// of them, so "source j has landed" is "at most (number of vector-memory operations issued after source j's load)
+// are outstanding".  Between the load of the first source and the read-out of the last one a kernel must
+// therefore issue NO other vector-memory instruction (loads of scales and zero-points are issued BEFORE the first
+// source; stores come after the last read-out), or `k` must count it.  The fan-in is at most 8, far below the 40
+// cases spelled out below (beyond them the wait degrades to vmcnt(0), which is always sufficient).
+//
+// Building with -DFC_PLAIN_LANDING_READS replaces the scheme by its plain equivalent, a full vmcnt(0) before an
+// ordinary LDS load that the compiler sees: slower, but free of hand-placed counts.  The build makes that variant
+// of the fused kernels as well (libfc_plainreads.so) and the GPU tests run the fused parity cases through both,
+// so that a compiler change that breaks the hand ordering shows up as a difference between the two.
+
 // Wait until at most `n` vector-memory operations of this wavefront are still
-// outstanding (they complete in issue order).  The compiler does not order LDS
-// reads after buffer-to-LDS loads by itself, so reads of a landing zone are
-// fenced explicitly; the "memory" clobber keeps the compiler from moving any
-// memory access across the wait.  `n` must be wave-uniform.
+// outstanding (they complete in issue order).  The "memory" clobber keeps the compiler
+// from moving any memory access across the wait.  `n` must be wave-uniform.
 #define FC_WAIT_VM_CASE(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
 __device__ __forceinline__ void wait_vmem_outstanding(int n)
 {
+#ifdef FC_PLAIN_LANDING_READS
+    n = 0;
+#endif
     switch (n) {
         FC_WAIT_VM_CASE(1) FC_WAIT_VM_CASE(2) FC_WAIT_VM_CASE(3) FC_WAIT_VM_CASE(4) FC_WAIT_VM_CASE(5)
         FC_WAIT_VM_CASE(6) FC_WAIT_VM_CASE(7) FC_WAIT_VM_CASE(8) FC_WAIT_VM_CASE(9) FC_WAIT_VM_CASE(10)
@@ -120,28 +140,33 @@ __device__ __forceinline__ void wait_vmem_outstanding(int n)
     }
 }
 #undef FC_WAIT_VM_CASE
+constexpr int kMaxCountedVmem = 40;      // largest count wait_vmem_outstanding spells out
 
-// 128-bit LDS read that the compiler's wait-count bookkeeping does not see.
-// (With an ordinary LDS load the compiler guards a landing-zone read by waiting
-// for ALL outstanding vector-memory operations in some control-flow shapes, and
-// by not waiting at all in others; the landing zone is therefore ordered by
-// hand: wait_vmem_outstanding before, lds_read_complete after.)  The value
+// 128-bit LDS read that the compiler's wait-count bookkeeping does not see.  The value
 // returned must not be used before lds_read_complete(v) has been called.
 // `byte_off` (a compile-time constant once the caller's loop is unrolled, at most 65535) goes into the
 // instruction's offset field, so one address register serves every landing slot of the wavefront.
 __device__ __forceinline__ u32x4 lds_read_b128_issue(const void *p, int byte_off = 0)
 {
+#ifdef FC_PLAIN_LANDING_READS
+    return *reinterpret_cast<const u32x4 *>(static_cast<const uint8_t *>(p) + byte_off);
+#else
     u32x4 v;
     const u32 addr = (u32)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(byte_off) : "memory");
     return v;
+#endif
 }
 
 // Waits for every LDS operation of the wavefront; `v` passes through so that
 // no use of it can be scheduled in front of the wait.
 __device__ __forceinline__ void lds_read_complete(u32x4 &v)
 {
+#ifdef FC_PLAIN_LANDING_READS
+    asm volatile("" : "+v"(v) : : "memory");
+#else
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v) : : "memory");
+#endif
 }
 
 // the compiler may not move memory operations across this point
@@ -994,6 +1019,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     constexpr int kTileElems = BT * EPL;
     constexpr int kOutBytes = EPL * BITS_OUT / 8;             // code bytes a lane writes: 8, 16 or 32
     static_assert(LPG >= 1 && LPG <= 256 && (LPG & (LPG - 1)) == 0, "lanes per group: a power of two up to 256");
+    static_assert(NSRC >= 1 && NSRC - 1 <= kMaxCountedVmem, "landing-zone waits count the loads of the later sources");
     constexpr int gw = LPG >= 64 ? 1 : 64 / LPG;              // groups per wavefront tile
     constexpr int gw_shift = __builtin_ctz((unsigned)gw);
     constexpr int entries = NSRC * gw;
@@ -1169,6 +1195,7 @@ __global__ __launch_bounds__(fused_block_threads(LPG)) void k_dequant_reduce_req
     __shared__ __attribute__((aligned(16))) uint8_t out_img[kOutBytes == 32 ? kWaves : 1]
                                                             [kOutBytes == 32 ? 2048 : 16];
     static_assert(LPG >= 1 && LPG <= 256 && (LPG & (LPG - 1)) == 0, "lanes per group: a power of two up to 256");
+    static_assert(NSRC >= 1 && NSRC - 1 <= kMaxCountedVmem, "landing-zone waits count the loads of the later sources");
     constexpr bool kSpansWaves = LPG > 64;
     __shared__ float slot[kSpansWaves ? kWaves : 1][2];       // cross-wavefront maximum (wide groups)
 

@@ -124,3 +124,62 @@ def test_fused_small_volumes_every_fan_in(fc, bits_in, bits_out, n_src):
             got.check()
             assert same_bits(got.t.cpu().numpy(), w_), "N=%d %dx%d %d->%d %s: %s" % (
                 n_src, t, h, bits_in, bits_out, part, first_diff(got.t.cpu().numpy(), w_))
+
+
+# The fused kernels read their landing zones with hand-ordered waits.  libfc_plainreads.so is the same library with
+# those reads compiled the plain way (full wait, compiler-visible LDS loads): both must give the oracle's bits for
+# every fan-in and bit-width pair, on narrow, wide and cross-wavefront groups, asymmetric and symmetric.
+@pytest.fixture(scope="module")
+def plain_lib():
+    import ctypes
+    import os
+    import paper_2412_04964_amd as m
+    path = os.path.join(os.path.dirname(m.lib_path()), "libfc_plainreads.so")
+    if not os.path.exists(path):
+        pytest.fail("%s missing: build with `python -m paper_2412_04964_amd.build`" % path)
+    L = ctypes.CDLL(path)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    L.fc_dequant_reduce_requant.argtypes = [vp, i64, vp, vp, i64, i32, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    L.fc_dequant_reduce_requant.restype = i32
+    L.fc_dequant_reduce_requant_sym.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32, vp, vp, vp]
+    L.fc_dequant_reduce_requant_sym.restype = i32
+    return L
+
+
+@pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_hand_ordered_and_plain_landing_reads_agree_with_the_oracle(fc, plain_lib, bits_in, bits_out, n_src):
+    t, h = 6, 8192
+    x = synth_inputs.make_partials(n_src, t, h, seed=900 + n_src, outlier_frac=0.01)
+    for group in (32, 128, 1024, 8192):
+        c, s, z = oracle_stage1(x, group, bits_in)
+        want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
+        cd, sd, zd = dev(c), dev(s), dev(z)
+        for which, L in (("hand-ordered", fc.lib()), ("plain", plain_lib)):
+            co = Guarded((t, h * bits_out // 8), torch.uint8)
+            so = Guarded((t, h // group), torch.float32)
+            zo = Guarded((t, h // group), torch.float32)
+            rc = L.fc_dequant_reduce_requant(cd.data_ptr(), cd.stride(0), sd.data_ptr(), zd.data_ptr(), sd.stride(0), n_src,
+                                             t, h, group, bits_in, bits_out, co.t.data_ptr(), so.t.data_ptr(),
+                                             zo.t.data_ptr(), _stream())
+            assert rc == 0
+            torch.cuda.synchronize()
+            for part, got, w_ in zip(("codes", "scales", "zeros"), (co, so, zo), want):
+                got.check()
+                assert same_bits(got.t.cpu().numpy(), w_), "%s reads, N=%d g=%d %d->%d %s: %s" % (
+                    which, n_src, group, bits_in, bits_out, part, first_diff(got.t.cpu().numpy(), w_))
+    # symmetric kernels share the staging
+    group = 128
+    parts = [oracle.quantize_sym(x[j], group, bits_in) for j in range(n_src)]
+    c = np.stack([p[0] for p in parts]); s = np.stack([p[1] for p in parts])
+    want = oracle.dequant_reduce_requant_sym(c, s, h, group, bits_in, bits_out)
+    cd, sd = dev(c), dev(s)
+    for which, L in (("hand-ordered", fc.lib()), ("plain", plain_lib)):
+        co = Guarded((t, h * bits_out // 8), torch.uint8)
+        so = Guarded((t, h // group), torch.float32)
+        rc = L.fc_dequant_reduce_requant_sym(cd.data_ptr(), cd.stride(0), sd.data_ptr(), sd.stride(0), n_src, t, h, group,
+                                             bits_in, bits_out, co.t.data_ptr(), so.t.data_ptr(), _stream())
+        assert rc == 0
+        torch.cuda.synchronize()
+        co.check(); so.check()
+        assert same_bits(co.t.cpu().numpy(), want[0]) and same_bits(so.t.cpu().numpy(), want[1]), which + " reads, symmetric"
