@@ -139,9 +139,15 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
     using S = RowShape<BITS, LOGH>;
     constexpr int EPL = S::EPL, T = S::T, P = S::P;
     constexpr int kPieces = EPL * 2 / 16;
-    __shared__ __attribute__((aligned(16))) uint8_t img[P][T / 64][kPieces * 1024];
-    __shared__ __attribute__((aligned(16))) float row[S::ROW_WORDS];
+    // the binary16 image of the row as it arrives and the padded fp32 row of the transform share their LDS (the
+    // image is dead once every thread has its values in registers): 37 KB instead of 53 KB per workgroup at
+    // hidden 8192, i.e. four resident workgroups per compute unit instead of three
+    constexpr int kImgBytes = P * (T / 64) * kPieces * 1024;
+    constexpr int kLdsBytes = kImgBytes > S::ROW_WORDS * 4 ? kImgBytes : S::ROW_WORDS * 4;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     __shared__ float slot[P][kBlockWaves][2];
+    uint8_t (*img)[T / 64][kPieces * 1024] = reinterpret_cast<uint8_t (*)[T / 64][kPieces * 1024]>(lds);
+    float *row = reinterpret_cast<float *>(lds);
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t e0 = (int64_t)blockIdx.x << LOGH;
@@ -170,6 +176,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
             }
         }
     }
+    __syncthreads();                                   // the image is read; its LDS becomes the row
 
     hadamard_row<BITS, LOGH>(v, row, tid);
     // Forward scaling fwd = 2^-ceil(n/2).  It is a power of two and nothing here is near the ends of
@@ -230,8 +237,12 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
     using S = RowShape<BITS, LOGH>;
     constexpr int EPL = S::EPL, T = S::T, P = S::P;
     constexpr int kPieces = EPL * 2 / 16;
-    __shared__ __attribute__((aligned(16))) uint8_t img[T / 64][kPieces * 1024];
-    __shared__ __attribute__((aligned(16))) float row[S::ROW_WORDS];
+    // the padded fp32 row and the binary16 image of the result share their LDS (see k_quantize_rot)
+    constexpr int kImgBytes = (T / 64) * kPieces * 1024;
+    constexpr int kLdsBytes = kImgBytes > S::ROW_WORDS * 4 ? kImgBytes : S::ROW_WORDS * 4;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
+    uint8_t (*img)[kPieces * 1024] = reinterpret_cast<uint8_t (*)[kPieces * 1024]>(lds);
+    float *row = reinterpret_cast<float *>(lds);
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t e0 = (int64_t)blockIdx.x << LOGH;
@@ -267,6 +278,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
     }
 
     hadamard_row<BITS, LOGH>(v, row, tid);
+    __syncthreads();                                   // the row is read; its LDS becomes the output image
     constexpr float inv = 1.0f / (float)(1 << (LOGH / 2));             // 2^-floor(n/2)
 
 #pragma unroll
