@@ -131,6 +131,11 @@ FC_API int fc_dequantize(const void *codes, const float *scales, const float *ze
  *   y_f16      out  binary16 [tokens, hidden]
  *   workspace  device scratch of at least fc_allreduce_sim_workspace_bytes(...)
  *              bytes, 16-byte aligned; contents on return are unspecified.
+ * Volumes that launching rather than memory bounds (at most 2^20 elements per partial, group <= 512)
+ * run as ONE kernel that keeps both quantizations in registers (the single fused kernel of Section
+ * 3.2.3, "Kernel Design", with identity exchanges); it evaluates the same operations in the same order,
+ * so the result is bit-identical to the three steps, and it does not touch the workspace (which must
+ * still be passed).
  */
 FC_API int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
                             int group, int bits_rs, int bits_ag, void *y_f16,

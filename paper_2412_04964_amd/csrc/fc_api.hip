@@ -179,6 +179,11 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
     if (!workspace || workspace_bytes < L.total) return FC_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FC_ERR_ALIGN;
 
+    // launch-bound volumes: the three steps in one kernel, bit-identical, nothing goes through the workspace
+    if (codec == fc::CODEC_ASYM && fc::allreduce_small_applies(n, group))
+        return hip_result(fc::launch_allreduce_small(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
+                                                     static_cast<hipStream_t>(hip_stream)));
+
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
     // the N partials are N*tokens rows of one tensor; when the workspace slabs need no padding they

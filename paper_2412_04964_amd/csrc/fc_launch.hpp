@@ -81,6 +81,13 @@ hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t t
 hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,
                                  int64_t tokens, int hidden, int group, void *y_f16, hipStream_t stream);
 
+// fc_small.hip: the whole all-reduce (asymmetric quantizer, fp32 metadata) in one launch, for launch-bound
+// volumes: at most kSmallAllreduceMaxElems elements per partial and groups of at most 512 elements.
+constexpr int64_t kSmallAllreduceMaxElems = (int64_t)1 << 20;
+bool allreduce_small_applies(int64_t n_elems, int group);
+hipError_t launch_allreduce_small(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
+                                  void *y_f16, hipStream_t stream);
+
 inline int log2_int(int v)
 {
     int s = 0;

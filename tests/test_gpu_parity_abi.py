@@ -183,3 +183,60 @@ def test_hand_ordered_and_plain_landing_reads_agree_with_the_oracle(fc, plain_li
         torch.cuda.synchronize()
         co.check(); so.check()
         assert same_bits(co.t.cpu().numpy(), want[0]) and same_bits(so.t.cpu().numpy(), want[1]), which + " reads, symmetric"
+
+
+# Volumes of at most 2^20 elements per partial with groups of at most 512 elements take fc_allreduce_sim's
+# one-launch kernel: same bits as the three separate entry points and as the oracle, for every fan-in, bit-width
+# pair and group size, with ragged last tiles, adversarial groups, and on both sides of the size limit.
+def _three_kernel_path(fc, xd, group, bits_rs, bits_ag):
+    stage1 = [fc.quantize(xd[j], group, bits_rs) for j in range(xd.shape[0])]
+    c = torch.stack([p[0] for p in stage1]); s = torch.stack([p[1] for p in stage1]); z = torch.stack([p[2] for p in stage1])
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, xd.shape[2], group, bits_rs, bits_ag)
+    return fc.dequantize(co, so, zo, xd.shape[2], group, bits_ag)
+
+
+@pytest.mark.parametrize("bits_rs,bits_ag", [(8, 8), (4, 4), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_one_launch_allreduce_every_fan_in_and_group(fc, bits_rs, bits_ag, n_src):
+    for (t, h, group) in [(8, 8192, 128), (3, 1056, 32), (5, 2112, 64), (7, 2304, 256), (2, 1536, 512), (1, 32, 32)]:
+        x = synth_inputs.make_partials(n_src, t, h, seed=50 * n_src + bits_rs + t, outlier_frac=0.02)
+        xd = dev(x.view(np.uint16)).view(torch.float16)
+        y = Guarded((t, h), torch.float16)
+        fc.allreduce_sim(xd, group, bits_rs, bits_ag, out=y.t)
+        y3 = _three_kernel_path(fc, xd, group, bits_rs, bits_ag)
+        torch.cuda.synchronize(); y.check()
+        got = y.t.cpu().numpy().view(np.uint16)
+        want = oracle.allreduce_sim(x, group, bits_rs, bits_ag).view(np.uint16)
+        what = "N=%d %dx%d g=%d %d->%d" % (n_src, t, h, group, bits_rs, bits_ag)
+        assert same_bits(got, want), what + " vs oracle: " + first_diff(got, want)
+        assert same_bits(got, y3.cpu().numpy().view(np.uint16)), what + " vs the three entry points"
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_one_launch_allreduce_adversarial_and_stress_values(fc, bits):
+    for group in (32, 128, 512):
+        a = synth_inputs.adversarial_groups(group, seed=3 + group)
+        x = np.stack([a, a[::-1].copy(), (-a.astype(np.float32)).astype(np.float16)])
+        for n in (1, 2, 3):
+            want = oracle.allreduce_sim(x[:n], group, bits, bits).view(np.uint16)
+            got = fc.allreduce_sim(dev(x[:n].view(np.uint16)).view(torch.float16), group, bits, bits)
+            torch.cuda.synchronize()
+            got = got.cpu().numpy().view(np.uint16)
+            assert same_bits(got, want), "adversarial g=%d b=%d n=%d: %s" % (group, bits, n, first_diff(got, want))
+    for kind in range(6):
+        x = synth_inputs.make_partials_stress(3, 24, 2048, seed=70 + kind, kind=kind)
+        want = oracle.allreduce_sim(x, 128, bits, bits).view(np.uint16)
+        got = fc.allreduce_sim(dev(x.view(np.uint16)).view(torch.float16), 128, bits, bits).cpu().numpy().view(np.uint16)
+        assert same_bits(got, want), "stress kind %d b=%d: %s" % (kind, bits, first_diff(got, want))
+
+
+def test_one_launch_allreduce_on_both_sides_of_its_size_limit(fc):
+    h, group = 8192, 128
+    for t in (128, 129):                                   # 2^20 elements per partial: one launch; above: three kernels
+        x = synth_inputs.make_partials(2, t, h, seed=t, outlier_frac=0.01)
+        xd = dev(x.view(np.uint16)).view(torch.float16)
+        got = fc.allreduce_sim(xd, group, 4, 8).cpu().numpy().view(np.uint16)
+        y3 = _three_kernel_path(fc, xd, group, 4, 8).cpu().numpy().view(np.uint16)
+        want = oracle.allreduce_sim(x, group, 4, 8).view(np.uint16)
+        assert same_bits(got, want), "t=%d: %s" % (t, first_diff(got, want))
+        assert same_bits(got, y3)
