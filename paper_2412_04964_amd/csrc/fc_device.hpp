@@ -279,6 +279,38 @@ __device__ __forceinline__ float dpp_max(float v)
     return r;
 }
 
+// Second half of a wavefront-wide reduction: every lane holds the min (max) of its row of 16 lanes.
+// row_bcast:15 gives rows 1 and 3 the value of the last lane of the row before them, row_bcast:31 gives rows 2
+// and 3 the value of lane 31; afterwards lane 31 holds the result of lanes 0-31 and lane 63 that of the whole
+// wavefront (lanes 32-63 after the first step alone).  Rows that a step does not address keep their value.
+template <bool IS_MIN, bool FULL>
+__device__ __forceinline__ float rows_reduce(float v)
+{
+    if constexpr (IS_MIN) {
+        asm("s_nop 1\n\tv_min_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+        if constexpr (FULL) asm("s_nop 1\n\tv_min_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+    } else {
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+        if constexpr (FULL) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+    }
+    return v;
+}
+
+// min (max) over the 32-lane half (lpg == 32) or the whole wavefront (lpg == 64) that a lane belongs to, given
+// the value already reduced over its row of 16 lanes
+template <bool IS_MIN>
+__device__ __forceinline__ float halves_or_wave(float v, int lpg, u32 lane)
+{
+    if (lpg >= 64) {
+        const float t = rows_reduce<IS_MIN, true>(v);
+        return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t), 63));
+    }
+    const float t = rows_reduce<IS_MIN, false>(v);
+    const float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t), 31));
+    const float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t), 63));
+    return lane < 32u ? lo : hi;
+}
+
 // All 64 lanes must be active when this is called.  The group spans `lpg`
 // adjacent lanes (a power of two, 1..64); LPG > 0 fixes it at compile time,
 // LPG == 0 reads the run-time value.
@@ -303,12 +335,9 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lpg_rt)
         mx = dpp_max<kDppRowMirror>(mx);
     }
     if (lpg >= 32) {
-        mn = fminf(mn, __shfl_xor(mn, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-    }
-    if (lpg >= 64) {
-        mn = fminf(mn, __shfl_xor(mn, 32));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const u32 lane = threadIdx.x & 63u;
+        mn = halves_or_wave<true>(mn, lpg, lane);
+        mx = halves_or_wave<false>(mx, lpg, lane);
     }
 }
 
@@ -544,8 +573,7 @@ __device__ __forceinline__ float group_max(float m, int lpg_rt)
     if (lpg >= 4) m = dpp_max<kDppQuadXor2>(m);
     if (lpg >= 8) m = dpp_max<kDppRowHalfMirror>(m);
     if (lpg >= 16) m = dpp_max<kDppRowMirror>(m);
-    if (lpg >= 32) m = fmaxf(m, __shfl_xor(m, 16));
-    if (lpg >= 64) m = fmaxf(m, __shfl_xor(m, 32));
+    if (lpg >= 32) m = halves_or_wave<false>(m, lpg, threadIdx.x & 63u);
     return m;
 }
 
@@ -1169,8 +1197,14 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     store_codes<kOutBytes>(word, rc, wave, lane, &out_img[kOutBytes == 32 ? wave : 0][0]);
     if ((tid & (LPG - 1)) == 0) {
         const u32 gi = (tid * EPL) >> group_shift;
-        store_f32(rs, gi * 4, HM ? __builtin_bit_cast(float, pack_meta(s, zf)) : s);
-        if constexpr (!HM) store_f32(rz, gi * 4, zf);
+        // One group per lane (32-element groups at 4 bit): a wavefront writes whole 256-byte runs of scales and of
+        // zero-points, and those stream best marked non-temporal like the codes (headline shape, g = 32: 48.2 ->
+        // 37.7 us).  Wider groups write 128 bytes or less per wavefront and array; there the default policy, which
+        // lets the L2 merge the pieces of a line, is the faster one (non-temporal: +1.4 us at g = 128).
+        constexpr int kMetaStorePolicy = LPG == 1 ? kStreamStorePolicy : 0;
+        const u32 first = HM ? pack_meta(s, zf) : __builtin_bit_cast(u32, s);
+        __builtin_amdgcn_raw_buffer_store_b32(first, rs, gi * 4, 0, kMetaStorePolicy);
+        if constexpr (!HM) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(u32, zf), rz, gi * 4, 0, kMetaStorePolicy);
     }
 }
 
