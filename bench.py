@@ -437,7 +437,7 @@ def main():
         "roofline": {
             "kernel": "k_dequant_reduce_requant%s<%d,%d,%d>%s" % ("_sym" if (sym or fp8) else "", w.bits_in, w.bits_out,
                                                                  N, " (E4M3)" if fp8 else " (binary16 metadata)" if cm else ""),
-            "bound": "hbm",
+            "bound": "hbm",                                  # the metric's own roofline: bytes against the HBM peak
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
