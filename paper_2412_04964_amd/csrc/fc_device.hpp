@@ -888,6 +888,37 @@ __device__ __forceinline__ void codes_minus_zero_fast(const u32 (&w)[4], const Z
     }
 }
 
+// v[e] = (q_e - z) * s for the lane's 128 bits of codes.  The widening of the binary16 difference folds into a
+// mixed-precision multiply-add with a zero addend: the differences are integers (never -0) and s is positive, so
+// adding +0 changes neither a nonzero product nor the sign of a zero one.
+template <int BITS>
+__device__ __forceinline__ void scaled_differences_fast(const u32 (&w)[4], const ZeroConst &c, float s,
+                                                        float (&v)[128 / BITS])
+{
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 p[4];
+            nibbles_minus_zero(w[k], c, p);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[8 * k + i] = fmaf((float)p[i].x, s, 0.0f);
+                v[8 * k + 4 + i] = fmaf((float)p[i].y, s, 0.0f);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 p[2];
+            bytes_minus_zero(w[k], c, p);
+            v[4 * k + 0] = fmaf((float)p[0].x, s, 0.0f);
+            v[4 * k + 2] = fmaf((float)p[0].y, s, 0.0f);
+            v[4 * k + 1] = fmaf((float)p[1].x, s, 0.0f);
+            v[4 * k + 3] = fmaf((float)p[1].y, s, 0.0f);
+        }
+    }
+}
+
 template <int BITS>
 __device__ __forceinline__ void codes_minus_zero_general(const u32 (&w)[4], float zf,
                                                          float (&d)[128 / BITS])

@@ -26,12 +26,12 @@ namespace fc {
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 
-// NB butterfly stages over the low NB bits of the register index, spans 1, 2, 4, ...
-template <int R, int NB>
+// Butterfly stages S0 ... NB-1 over the low NB bits of the register index, spans 2^S0, 2^(S0+1), ...
+template <int R, int NB, int S0 = 0>
 __device__ __forceinline__ void butterflies(float (&x)[R])
 {
 #pragma unroll
-    for (int s = 0; s < NB; ++s)
+    for (int s = S0; s < NB; ++s)
 #pragma unroll
         for (int q = 0; q < R; ++q)
             if (!(q & (1 << s))) {
@@ -39,6 +39,15 @@ __device__ __forceinline__ void butterflies(float (&x)[R])
                 x[q] = a + b;
                 x[q | (1 << s)] = a - b;
             }
+}
+
+// First stage (span 1) on a pair of binary16 inputs held in one word: (lo + hi, lo - hi) in fp32.  Widening a
+// binary16 number is exact, so a mixed-precision multiply-add lo * 1 +- hi rounds the same real sum once, as the
+// conversion followed by an fp32 add does: one instruction per output instead of a conversion and an add.
+__device__ __forceinline__ void first_stage(u32 pair, float &sum, float &diff)
+{
+    asm("v_fma_mix_f32 %0, %1, 1.0, %1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(sum) : "v"(pair));
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(diff) : "v"(pair));
 }
 
 // word position of element e in the padded LDS row: 4 extra words per lane segment of 2^LE elements
@@ -97,14 +106,15 @@ struct RowShape {
     static_assert(T >= 64 && (P == 1 || P == 2), "rows of 2048 to 8192 elements");
 };
 
-// In-place transform of the row held as v[p][i] = element (p*T + tid)*EPL + i.
-template <int BITS, int LOGH, int NP, int NE>
+// In-place transform of the row held as v[p][i] = element (p*T + tid)*EPL + i.  With S0 = 1 the caller has
+// already applied the first stage (span 1).
+template <int BITS, int LOGH, int S0, int NP, int NE>
 __device__ __forceinline__ void hadamard_row(float (&v)[NP][NE], float *row, u32 tid)
 {
     using S = RowShape<BITS, LOGH>;
     static_assert(NP == S::P && NE == S::EPL, "row held as v[P][EPL]");
 #pragma unroll
-    for (int p = 0; p < S::P; ++p) butterflies<S::EPL, S::LE>(v[p]);
+    for (int p = 0; p < S::P; ++p) butterflies<S::EPL, S::LE, S0>(v[p]);
 #pragma unroll
     for (int p = 0; p < S::P; ++p) {
         u32x4 *dst = reinterpret_cast<u32x4 *>(row + padded<S::LE>((p * S::T + tid) * S::EPL));
@@ -169,16 +179,12 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
         for (int k = 0; k < kPieces; ++k) {
             const u32x4 a = mine[k];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const h2 h = as_h2(a[i]);
-                v[p][8 * k + 2 * i] = (float)h.x;
-                v[p][8 * k + 2 * i + 1] = (float)h.y;
-            }
+            for (int i = 0; i < 4; ++i) first_stage(a[i], v[p][8 * k + 2 * i], v[p][8 * k + 2 * i + 1]);
         }
     }
     __syncthreads();                                   // the image is read; its LDS becomes the row
 
-    hadamard_row<BITS, LOGH>(v, row, tid);
+    hadamard_row<BITS, LOGH, 1>(v, row, tid);
     // Forward scaling fwd = 2^-ceil(n/2).  It is a power of two and nothing here is near the ends of
     // the fp32 range (the transformed values are multiples of 2^-24 below 2^30), so scaling commutes
     // with every rounding: instead of scaling all values, the group's min and max are scaled (which
@@ -257,27 +263,31 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
         const int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
         const float s = scales[gi];
         const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, lane_in_row * 16, 0, kStreamLoadPolicy);
-        float d[EPL];
         if constexpr (CODEC == kFp8) {
             const u32 w[4] = {a[0], a[1], a[2], a[3]};
+            float d[EPL];
             decode_fp8(w, d);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) v[p][i] = d[i] * s;
         } else if constexpr (CODEC == kSym) {
             const u32 w[4] = {to_offset_binary<BITS>(a[0]), to_offset_binary<BITS>(a[1]),
                               to_offset_binary<BITS>(a[2]), to_offset_binary<BITS>(a[3])};
-            codes_minus_zero_fast<BITS>(w, sym_zero_const<BITS>(), d);
+            scaled_differences_fast<BITS>(w, sym_zero_const<BITS>(), s, v[p]);
         } else {
             const float zf = zeros[gi];
             const u32 w[4] = {a[0], a[1], a[2], a[3]};
-            if (__builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0)
-                codes_minus_zero_fast<BITS>(w, unpack_zero_const(pack_zero_const(zf)), d);
-            else
+            if (__builtin_amdgcn_ballot_w64(!zero_is_fast(zf)) == 0) {
+                scaled_differences_fast<BITS>(w, unpack_zero_const(pack_zero_const(zf)), s, v[p]);
+            } else {
+                float d[EPL];
                 codes_minus_zero_general<BITS>(w, zf, d);
-        }
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) v[p][i] = d[i] * s;
+                for (int i = 0; i < EPL; ++i) v[p][i] = d[i] * s;
+            }
+        }
     }
 
-    hadamard_row<BITS, LOGH>(v, row, tid);
+    hadamard_row<BITS, LOGH, 0>(v, row, tid);
     __syncthreads();                                   // the row is read; its LDS becomes the output image
     constexpr float inv = 1.0f / (float)(1 << (LOGH / 2));             // 2^-floor(n/2)
 
