@@ -131,11 +131,11 @@ FC_API int fc_dequantize(const void *codes, const float *scales, const float *ze
  *   y_f16      out  binary16 [tokens, hidden]
  *   workspace  device scratch of at least fc_allreduce_sim_workspace_bytes(...)
  *              bytes, 16-byte aligned; contents on return are unspecified.
- * Volumes that launching rather than memory bounds (at most 2^20 elements per partial, group <= 512)
- * run as ONE kernel that keeps both quantizations in registers (the single fused kernel of Section
- * 3.2.3, "Kernel Design", with identity exchanges); it evaluates the same operations in the same order,
- * so the result is bit-identical to the three steps, and it does not touch the workspace (which must
- * still be passed).
+ * With groups of at most 1024 elements the call runs as ONE kernel that keeps both quantizations in
+ * registers (the single fused kernel of Section 3.2.3, "Kernel Design", with identity exchanges): the
+ * partials are read once and the result is written once, 2 n_src + 2 bytes per element.  It evaluates
+ * the same operations in the same order, so the result is bit-identical to the three steps, and it
+ * does not touch the workspace (which must still be passed).  Wider groups run as the three steps.
  */
 FC_API int fc_allreduce_sim(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
                             int group, int bits_rs, int bits_ag, void *y_f16,
@@ -147,8 +147,8 @@ FC_API size_t fc_allreduce_sim_workspace_bytes(int n_src, int64_t tokens, int64_
 
 /*
  * fc_allreduce_sim for callers that cannot allocate device memory or keep a workspace (code
- * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the same
- * kernels, with the intermediate codes, scales and zero-points in a fixed array of
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): always the
+ * three steps, with the intermediate codes, scales and zero-points in a fixed array of
  * FC_STATIC_SCRATCH_BYTES that lives in the library's device image (one copy per GPU, held until
  * the process ends).  The call allocates and frees nothing.  Same arguments, results and errors
  * as fc_allreduce_sim, plus:

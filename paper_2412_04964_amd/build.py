@@ -42,7 +42,7 @@ FLAGS = [
 
 # (source, object suffix, extra defines)
 UNITS = [("fc_api.hip", "api", []), ("fc_codec.hip", "codec", []), ("fc_wide.hip", "wide", []),
-         ("fc_rot.hip", "rot", []), ("fc_small.hip", "small", [])]
+         ("fc_rot.hip", "rot", []), ("fc_small.hip", "small", []), ("fc_sim.hip", "sim", [])]
 BENCH_UNITS = [("fc_bench.hip", "bench", [])]
 for _bi in (4, 8):
     for _bo in (4, 8):

@@ -163,9 +163,11 @@ int dequantize_impl(int codec, const void *codes, const float *scales, const flo
                                             static_cast<hipStream_t>(hip_stream)));
 }
 
+// one_launch: whether the single-kernel forms (which leave the workspace untouched) may stand in for the
+// three-kernel sequence
 int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, int64_t hidden,
                        int group, int bits_rs, int bits_ag, void *y_f16,
-                       void *workspace, size_t workspace_bytes, void *hip_stream)
+                       void *workspace, size_t workspace_bytes, void *hip_stream, bool one_launch = true)
 {
     int64_t n = 0;
     const int rc = check_shape(tokens, hidden, group, bits_rs, &n);
@@ -179,10 +181,16 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
     if (!workspace || workspace_bytes < L.total) return FC_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FC_ERR_ALIGN;
 
-    // launch-bound volumes: the three steps in one kernel, bit-identical, nothing goes through the workspace
-    if (codec == fc::CODEC_ASYM && fc::allreduce_small_applies(n, group))
-        return hip_result(fc::launch_allreduce_small(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
-                                                     static_cast<hipStream_t>(hip_stream)));
+    // the three steps in one kernel, bit-identical, nothing goes through the workspace: one form for launch-bound
+    // volumes (the partials' quantizations spread over wavefronts), one for bandwidth-bound volumes
+    if (one_launch && codec == fc::CODEC_ASYM) {
+        if (fc::allreduce_small_applies(n, group))
+            return hip_result(fc::launch_allreduce_small(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
+                                                         static_cast<hipStream_t>(hip_stream)));
+        if (fc::allreduce_fused_applies(n, group))
+            return hip_result(fc::launch_allreduce_fused(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
+                                                         static_cast<hipStream_t>(hip_stream)));
+    }
 
     char *ws = static_cast<char *>(workspace);
     const char *x = static_cast<const char *>(x_f16);
@@ -362,8 +370,10 @@ int fc_allreduce_sim_static(const void *x_f16, int n_src, int64_t tokens, int64_
     if (sc != FC_OK) return sc;
     // nothing in the scratch has to start at zero: every byte a kernel reads there was written by
     // the kernel before it in this call
+    // always the three-kernel sequence through the scratch array (the single-kernel forms need no intermediates
+    // at all; fc_allreduce_sim takes them where they apply)
     return allreduce_sim_impl(fc::CODEC_ASYM, x_f16, n_src, tokens, hidden, group, bits_rs, bits_ag, y_f16,
-                              ws, (size_t)FC_STATIC_SCRATCH_BYTES, hip_stream);
+                              ws, (size_t)FC_STATIC_SCRATCH_BYTES, hip_stream, false);
 }
 
 int fc_allreduce_sim_sym(const void *x_f16, int n_src, int64_t tokens, int64_t hidden,

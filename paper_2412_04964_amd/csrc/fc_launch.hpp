@@ -88,6 +88,12 @@ bool allreduce_small_applies(int64_t n_elems, int group);
 hipError_t launch_allreduce_small(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
                                   void *y_f16, hipStream_t stream);
 
+// fc_sim.hip: the same in one launch for volumes that memory bandwidth bounds (the N binary16 partials are read once,
+// the binary16 result is written once, nothing else touches memory); groups of at most 1024 elements.
+bool allreduce_fused_applies(int64_t n_elems, int group);
+hipError_t launch_allreduce_fused(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
+                                  void *y_f16, hipStream_t stream);
+
 inline int log2_int(int v)
 {
     int s = 0;

@@ -1,0 +1,140 @@
+"""GPU parity of the single-kernel all-reduce for bandwidth-bound volumes (fc_allreduce_sim above 2^20 elements per
+partial, groups of at most 1024 elements) against the CPU oracle, bit for bit, and against the three-kernel sequence
+(fc_quantize x N, fc_dequant_reduce_requant, fc_dequantize called one by one through the binding).  Volumes are just
+above the threshold so that the oracle finishes in a fraction of a second per case."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SMALL_LIMIT = 1 << 20        # elements per partial up to which fc_allreduce_sim takes the launch-bound kernel
+
+
+@pytest.fixture(scope="module")
+def fc():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests selected but no GPU is visible")
+    import paper_2412_04964_amd as m
+    m.lib()
+    return m
+
+
+def dev16(x):
+    return torch.from_numpy(np.ascontiguousarray(x).view(np.uint16)).cuda().view(torch.float16)
+
+
+def run_sim(fc, x, group, b_rs, b_ag):
+    n, t, h = x.shape
+    assert t * h > SMALL_LIMIT, "the case must reach the bandwidth-bound kernel"
+    guard = 64
+    raw = torch.full((t * h + 2 * guard,), 7.0, dtype=torch.float16, device="cuda")
+    y = raw[guard:guard + t * h].view(t, h)
+    fc.allreduce_sim(dev16(x), group, b_rs, b_ag, out=y)
+    torch.cuda.synchronize()
+    edge = raw.cpu().numpy()
+    assert (edge[:guard] == 7.0).all() and (edge[guard + t * h:] == 7.0).all(), "write outside the output"
+    return y.cpu().numpy()
+
+
+def three_steps(fc, x, group, b_rs, b_ag):
+    n, t, h = x.shape
+    xd = dev16(x)
+    parts = [fc.quantize(xd[j], group, b_rs) for j in range(n)]
+    c = torch.stack([p[0] for p in parts]); s = torch.stack([p[1] for p in parts]); z = torch.stack([p[2] for p in parts])
+    co, so, zo = fc.dequant_reduce_requant(c, s, z, h, group, b_rs, b_ag)
+    y = fc.dequantize(co, so, zo, h, group, b_ag)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def check(got, want, what):
+    g = np.ascontiguousarray(got).view(np.uint16); w = np.ascontiguousarray(want).view(np.uint16)
+    if g.tobytes() != w.tobytes():
+        idx = np.flatnonzero(g.ravel() != w.ravel())
+        raise AssertionError("%s: %d mismatches, first at %s: gpu=%s ref=%s" % (
+            what, idx.size, idx[:5], got.ravel()[idx[:5]], want.ravel()[idx[:5]]))
+
+
+@pytest.mark.parametrize("bits_rs,bits_ag", [(4, 4), (8, 8), (4, 8), (8, 4)])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_fan_in_and_bit_width_pair(fc, bits_rs, bits_ag, n_src):
+    # 129 rows of 8192: 516 whole workgroup tiles of 2048 elements; 1% outlier channels as in the workloads
+    x = synth_inputs.make_partials(n_src, 129, 8192, seed=100 + n_src, outlier_frac=0.01)
+    got = run_sim(fc, x, 128, bits_rs, bits_ag)
+    check(got, oracle.allreduce_sim(x, 128, bits_rs, bits_ag), "N=%d %d->%d" % (n_src, bits_rs, bits_ag))
+
+
+RAGGED = [(t, h, g) for (t, h) in ((257, 5120), (1025, 1024), (911, 1152), (1000, 1056))
+          for g in (32, 64, 128, 256, 512, 1024) if h % g == 0]
+
+
+@pytest.mark.parametrize("tokens,hidden,group", RAGGED)
+def test_group_sizes_and_ragged_tails(fc, tokens, hidden, group):
+    # 257 x 5120 and 1025 x 1024 end after the first wavefront of a workgroup tile, 911 x 1152 and 1000 x 1056 in
+    # the middle of a wavefront
+    x = synth_inputs.make_partials(3, tokens, hidden, seed=group + tokens, outlier_frac=0.01)
+    for b_rs, b_ag in ((4, 4), (8, 8)):
+        got = run_sim(fc, x, group, b_rs, b_ag)
+        check(got, oracle.allreduce_sim(x, group, b_rs, b_ag), "g=%d %dx%d %d->%d" % (group, tokens, hidden, b_rs, b_ag))
+
+
+@pytest.mark.parametrize("kind", range(synth_inputs.STRESS_KINDS))
+def test_corner_reaching_distributions(fc, kind):
+    # per-row scales over 22 octaves, bands on large offsets (zero-points in the hundreds of thousands),
+    # half-integers (ties), sparse spikes, micro-noise on constants
+    for n_src, group in ((2, 32), (4, 128), (8, 1024)):
+        x = synth_inputs.make_partials_stress(n_src, 130, 8192, kind, seed=7 * kind + n_src)
+        for b_rs, b_ag in ((4, 4), (8, 8), (4, 8)):
+            got = run_sim(fc, x, group, b_rs, b_ag)
+            check(got, oracle.allreduce_sim(x, group, b_rs, b_ag),
+                  "kind %d N=%d g=%d %d->%d" % (kind, n_src, group, b_rs, b_ag))
+
+
+@pytest.mark.parametrize("group", [32, 128, 512])
+def test_hand_picked_hard_groups(fc, group):
+    # constant, one-sided, zero, tiny-range-on-offset, binary16-extreme and subnormal groups, tiled to the volume;
+    # the partials carry the rows in different orders so that hard groups meet ordinary ones in the sum
+    rows = synth_inputs.adversarial_groups(group, seed=group)              # [r, 8 * group]
+    hidden = rows.shape[1]
+    reps = SMALL_LIMIT // (rows.shape[0] * hidden) + 2
+    base = np.tile(rows, (reps, 1))
+    x = np.stack([np.roll(base, j, axis=0) if j % 2 == 0 else np.roll(base[:, ::-1].copy(), j, axis=0)
+                  for j in range(4)])
+    for b_rs, b_ag in ((4, 4), (8, 8), (8, 4)):
+        got = run_sim(fc, x, group, b_rs, b_ag)
+        check(got, oracle.allreduce_sim(x, group, b_rs, b_ag), "hard groups g=%d %d->%d" % (group, b_rs, b_ag))
+
+
+@pytest.mark.parametrize("n_src,group,bits", [(4, 128, 4), (8, 64, 4), (2, 256, 8)])
+def test_identical_to_the_three_kernel_sequence(fc, n_src, group, bits):
+    x = synth_inputs.make_partials(n_src, 160, 8192, seed=n_src * group, outlier_frac=0.01)
+    check(run_sim(fc, x, group, bits, bits), three_steps(fc, x, group, bits, bits), "one launch vs three")
+
+
+def test_under_graph_capture_and_replay(fc):
+    # the call only enqueues one kernel: captured once, replayed on new inputs with eager work in between
+    n, t, h, g = 4, 136, 8192, 128
+    xd = torch.zeros((n, t, h), dtype=torch.float16, device="cuda")
+    y = torch.zeros((t, h), dtype=torch.float16, device="cuda")
+    ws = torch.empty(fc.allreduce_sim_workspace_bytes(n, t, h, g, 4, 4), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fc.allreduce_sim(xd, g, 4, 4, out=y, workspace=ws)           # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fc.allreduce_sim(xd, g, 4, 4, out=y, workspace=ws)
+    for rep in range(3):
+        x = synth_inputs.make_partials(n, t, h, seed=900 + rep, outlier_frac=0.01)
+        xd.copy_(dev16(x))
+        _ = (xd.float().sum()).item()                                    # eager work and a synchronization
+        graph.replay()
+        torch.cuda.synchronize()
+        check(y.cpu().numpy(), oracle.allreduce_sim(x, g, 4, 4), "replay %d" % rep)
