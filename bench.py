@@ -347,17 +347,24 @@ def main():
         probe_s = p0.elapsed_time(p1) * 1e-3 / p_reps
         del PC, PS, PZ
 
-    # The whole all-reduce as the library runs it (fc_allreduce_sim): with the asymmetric quantizer and groups of at
+    # The whole all-reduce as the library runs it (fc_allreduce_sim and its counterparts): with groups of at
     # most 1024 elements that is ONE launch which reads the N partials and writes the result, nothing else.  Timed
     # over the same rotating buffer sets; launch-bound volumes replay a HIP graph of B calls like the stages above.
     sim_s = None
-    if w.quantizer == "asym" and not w.rotate and g <= 1024:
+    if not w.rotate and g <= 1024:
         WS = torch.empty(max(16, fc.allreduce_sim_workspace_bytes(N, T, H, g, w.bits_in, w.bits_out)),
                          dtype=torch.uint8, device=dev)
 
         def sim_round():
             for k in range(B):
-                fc.allreduce_sim(X[k], g, w.bits_in, w.bits_out, out=Y[k], workspace=WS)
+                if fp8:
+                    fc.allreduce_sim_fp8(X[k], g, out=Y[k], workspace=WS)
+                elif sym:
+                    fc.allreduce_sim_sym(X[k], g, w.bits_in, w.bits_out, out=Y[k], workspace=WS)
+                elif cm:
+                    fc.allreduce_sim_cmeta(X[k], g, w.bits_in, w.bits_out, out=Y[k], workspace=WS)
+                else:
+                    fc.allreduce_sim(X[k], g, w.bits_in, w.bits_out, out=Y[k], workspace=WS)
 
         sim_round()
         torch.cuda.synchronize()

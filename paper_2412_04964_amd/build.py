@@ -42,7 +42,9 @@ FLAGS = [
 
 # (source, object suffix, extra defines)
 UNITS = [("fc_api.hip", "api", []), ("fc_codec.hip", "codec", []), ("fc_wide.hip", "wide", []),
-         ("fc_rot.hip", "rot", []), ("fc_small.hip", "small", []), ("fc_sim.hip", "sim", [])]
+         ("fc_rot.hip", "rot", []), ("fc_small.hip", "small", [])]
+for _c in range(4):      # one unit per quantizer: asymmetric, symmetric, FP8, asymmetric with binary16 metadata
+    UNITS.append(("fc_sim.hip", "sim_%d" % _c, ["-DFC_SIM_CODEC=%d" % _c]))
 BENCH_UNITS = [("fc_bench.hip", "bench", [])]
 for _bi in (4, 8):
     for _bo in (4, 8):

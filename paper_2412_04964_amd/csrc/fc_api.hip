@@ -182,13 +182,14 @@ int allreduce_sim_impl(int codec, const void *x_f16, int n_src, int64_t tokens, 
     if (!aligned16(workspace)) return FC_ERR_ALIGN;
 
     // the three steps in one kernel, bit-identical, nothing goes through the workspace: one form for launch-bound
-    // volumes (the partials' quantizations spread over wavefronts), one for bandwidth-bound volumes
-    if (one_launch && codec == fc::CODEC_ASYM) {
-        if (fc::allreduce_small_applies(n, group))
+    // volumes (asymmetric quantizer; the partials' quantizations spread over wavefronts), one for bandwidth-bound
+    // volumes (every quantizer)
+    if (one_launch) {
+        if (codec == fc::CODEC_ASYM && fc::allreduce_small_applies(n, group))
             return hip_result(fc::launch_allreduce_small(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
                                                          static_cast<hipStream_t>(hip_stream)));
         if (fc::allreduce_fused_applies(n, group))
-            return hip_result(fc::launch_allreduce_fused(bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
+            return hip_result(fc::launch_allreduce_fused(codec, bits_rs, bits_ag, x_f16, n_src, n, group, y_f16,
                                                          static_cast<hipStream_t>(hip_stream)));
     }
 

@@ -88,11 +88,31 @@ bool allreduce_small_applies(int64_t n_elems, int group);
 hipError_t launch_allreduce_small(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
                                   void *y_f16, hipStream_t stream);
 
-// fc_sim.hip: the same in one launch for volumes that memory bandwidth bounds (the N binary16 partials are read once,
-// the binary16 result is written once, nothing else touches memory); groups of at most 1024 elements.
-bool allreduce_fused_applies(int64_t n_elems, int group);
-hipError_t launch_allreduce_fused(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
-                                  void *y_f16, hipStream_t stream);
+// fc_sim.hip (one translation unit per quantizer): the same in one launch for volumes that memory bandwidth bounds
+// (the N binary16 partials are read once, the binary16 result is written once, nothing else touches memory);
+// groups of at most 1024 elements, every quantizer.
+constexpr int kFusedAllreduceMaxGroup = 1024;         // one wavefront's 64 lanes x 16 elements
+constexpr int kFusedAllreduceTileElems = 2048;        // one workgroup; the tile count must fit the 32-bit workgroup index
+inline bool allreduce_fused_applies(int64_t n_elems, int group)
+{
+    return group <= kFusedAllreduceMaxGroup && n_elems / kFusedAllreduceTileElems < 0x7FFFFFFF;
+}
+#define FC_DECLARE_SIM(name)                                                                                       \
+    hipError_t launch_allreduce_fused_##name(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, \
+                                             int group, void *y_f16, hipStream_t stream);
+FC_DECLARE_SIM(asym) FC_DECLARE_SIM(sym) FC_DECLARE_SIM(fp8) FC_DECLARE_SIM(cmeta)
+#undef FC_DECLARE_SIM
+inline hipError_t launch_allreduce_fused(int codec, int bits_rs, int bits_ag, const void *x_f16, int n_src,
+                                         int64_t n_elems, int group, void *y_f16, hipStream_t stream)
+{
+    switch (codec) {
+    case CODEC_ASYM: return launch_allreduce_fused_asym(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+    case CODEC_SYM: return launch_allreduce_fused_sym(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+    case CODEC_FP8: return launch_allreduce_fused_fp8(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+    case CODEC_ASYMH: return launch_allreduce_fused_cmeta(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
 
 inline int log2_int(int v)
 {

@@ -24,6 +24,14 @@
 //    zero-point of a sum can be any fp32 integer: u = rint(acc * (1/s')) + z', q = clamp(u, 0, qmax),
 //    y = half((q - z') * s').
 //
+//  * the other quantizers (one translation unit per quantizer, selected by FC_SIM_CODEC).  Symmetric (Eq. 3-4):
+//    max|x| of a lane is max(|min|, |max|) of its packed min / max; neither clamp of Eq. 4 can act on a group's own
+//    values, so the first stage contributes rint(x * (1/s)) itself, and the second stage adds +0 to its rint so that
+//    a code of zero dequantizes to +0 as the stored integer does.  FP8: both stages go through the same conversion
+//    instructions as the stand-alone kernels (the format keeps the sign of zero).  Binary16 metadata: group_params
+//    rounds the scale and the zero-point as the stored word does; the zero-point stays an integer below 2^17, so
+//    the median-of-three form of the first stage remains exact, lower clamp included.
+//
 // Decomposition: a lane owns 16 consecutive elements (two 128-bit pieces of binary16 per partial), a wavefront
 // 1024, a workgroup of two wavefronts 2048; a group of g <= 1024 elements is g/16 adjacent lanes.  At wavefront
 // start all N x 2 KB of the tile are requested as buffer-to-LDS loads (nothing sits in vector registers while in
@@ -38,6 +46,8 @@ constexpr int kSimLaneElems = 16;
 constexpr int kSimWaveElems = 64 * kSimLaneElems;
 constexpr int kSimBlockThreads = 128;
 constexpr int kSimTileElems = kSimBlockThreads * kSimLaneElems;
+static_assert(kSimWaveElems == kFusedAllreduceMaxGroup && kSimTileElems == kFusedAllreduceTileElems,
+              "the launcher's applicability test describes this decomposition");
 
 // Packed binary16 min / max as single instructions (the compiler's own sequence first canonicalizes each input
 // with a v_pk_max x, x; the inputs here come from memory and the result only has to be one of them).
@@ -54,14 +64,16 @@ __device__ __forceinline__ h2 pk_max(h2 a, h2 b)
     return r;
 }
 
-template <int BITS_RS, int BITS_AG, int NSRC, int LPG>
+template <int CODEC, int BITS_RS, int BITS_AG, int NSRC, int LPG>
 __global__ __launch_bounds__(kSimBlockThreads) void k_allreduce_fused(const uint16_t *__restrict__ x, int64_t n_elems,
                                                                      int lpg, uint16_t *__restrict__ y)
 {
     constexpr int E = kSimLaneElems;
     constexpr int kZone = E * 2 * 64;                                  // bytes of one partial per wavefront: 2 KB
     constexpr int kWaves = kSimBlockThreads / 64;
+    constexpr bool HM = CODEC == kAsymH;
     static_assert(2 * (NSRC - 1) <= kMaxCountedVmem, "landing-zone waits count the loads of the later sources");
+    static_assert(CODEC != kFp8 || (BITS_RS == 8 && BITS_AG == 8), "E4M3 codes are bytes");
     __shared__ __attribute__((aligned(16))) uint8_t landing[kWaves][NSRC][kZone];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -97,41 +109,79 @@ __global__ __launch_bounds__(kSimBlockThreads) void k_allreduce_fused(const uint
             hi = pk_max(hi, p[k]);
         }
         float mn = fminf((float)lo.x, (float)lo.y), mx = fmaxf((float)hi.x, (float)hi.y);
-        group_minmax<LPG>(mn, mx, lpg);
-        float s, inv, zf;
-        group_params<BITS_RS>(mn, mx, s, inv, zf);
-        const float d_lo = 0.0f - zf, d_hi = (float)((1 << BITS_RS) - 1) - zf;
+        float s, inv;
+        if constexpr (is_asym(CODEC)) {
+            group_minmax<LPG>(mn, mx, lpg);
+            float zf;
+            group_params<BITS_RS, HM>(mn, mx, s, inv, zf);
+            const float d_lo = 0.0f - zf, d_hi = (float)((1 << BITS_RS) - 1) - zf;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const float t0 = rintf(fmaf((float)p[k].x, inv, 0.0f));
-            const float t1 = rintf(fmaf((float)p[k].y, inv, 0.0f));
-            acc[2 * k] = fmaf(__builtin_amdgcn_fmed3f(t0, d_lo, d_hi), s, acc[2 * k]);
-            acc[2 * k + 1] = fmaf(__builtin_amdgcn_fmed3f(t1, d_lo, d_hi), s, acc[2 * k + 1]);
+            for (int k = 0; k < 8; ++k) {
+                const float t0 = rintf(fmaf((float)p[k].x, inv, 0.0f));
+                const float t1 = rintf(fmaf((float)p[k].y, inv, 0.0f));
+                acc[2 * k] = fmaf(__builtin_amdgcn_fmed3f(t0, d_lo, d_hi), s, acc[2 * k]);
+                acc[2 * k + 1] = fmaf(__builtin_amdgcn_fmed3f(t1, d_lo, d_hi), s, acc[2 * k + 1]);
+            }
+        } else {
+            const float amax = group_max<LPG>(fmaxf(fabsf(mn), fabsf(mx)), lpg);
+            if constexpr (CODEC == kSym) {
+                group_params_sym<BITS_RS>(amax, s, inv);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    acc[2 * k] = fmaf(rintf(fmaf((float)p[k].x, inv, 0.0f)), s, acc[2 * k]);
+                    acc[2 * k + 1] = fmaf(rintf(fmaf((float)p[k].y, inv, 0.0f)), s, acc[2 * k + 1]);
+                }
+            } else {
+                group_params_absmax<448>(amax, s, inv);
+                float v[E];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    v[2 * k] = (float)p[k].x;
+                    v[2 * k + 1] = (float)p[k].y;
+                }
+                u32 word[4];
+                pack_lane_fp8<E>(v, inv, word);
+                accumulate_fp8(word, s, acc);
+            }
         }
         pin_values(acc);              // source j is folded in before source j+1 is waited for
     }
 
-    // FinegrainedQuantize of the sums and the final Dequantize
-    float mn, mx, s, inv, zf;
-    lane_minmax(acc, mn, mx);
-    group_minmax<LPG>(mn, mx, lpg);
-    group_params<BITS_AG>(mn, mx, s, inv, zf);
-    constexpr float qmax = (float)((1 << BITS_AG) - 1);
+    // FinegrainedQuantize of the sums and the final Dequantize: d[i] = the dequantized code before the scale
+    float s, inv, d[E];
+    if constexpr (is_asym(CODEC)) {
+        float mn, mx, zf;
+        lane_minmax(acc, mn, mx);
+        group_minmax<LPG>(mn, mx, lpg);
+        group_params<BITS_AG, HM>(mn, mx, s, inv, zf);
+        constexpr float qmax = (float)((1 << BITS_AG) - 1);
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            const float u = rintf(acc[i] * inv) + zf;
+            d[i] = __builtin_amdgcn_fmed3f(u, 0.0f, qmax) - zf;
+        }
+    } else {
+        const float amax = group_max<LPG>(lane_absmax(acc), lpg);
+        if constexpr (CODEC == kSym) {
+            group_params_sym<BITS_AG>(amax, s, inv);
+#pragma unroll
+            for (int i = 0; i < E; ++i) d[i] = rintf(acc[i] * inv) + 0.0f;
+        } else {
+            group_params_absmax<448>(amax, s, inv);
+            u32 word[4];
+            pack_lane_fp8<E>(acc, inv, word);
+            decode_fp8(word, d);
+        }
+    }
     u32x4 *mine = reinterpret_cast<u32x4 *>(&landing[wave][0][lane * (E * 2)]);
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         u32x4 out;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float d[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float u = rintf(acc[8 * k + 2 * i + h] * inv) + zf;
-                d[h] = __builtin_amdgcn_fmed3f(u, 0.0f, qmax) - zf;
-            }
             h2 r;
-            r.x = (_Float16)(d[0] * s);
-            r.y = (_Float16)(d[1] * s);
+            r.x = (_Float16)(d[8 * k + 2 * i] * s);
+            r.y = (_Float16)(d[8 * k + 2 * i + 1] * s);
             out[i] = as_u32(r);
         }
         mine[k] = out;
@@ -144,7 +194,13 @@ __global__ __launch_bounds__(kSimBlockThreads) void k_allreduce_fused(const uint
     }
 }
 
+#ifndef FC_SIM_CODEC
+#error "compile with -DFC_SIM_CODEC=0..3 (kAsym, kSym, kFp8, kAsymH): one translation unit per quantizer"
+#endif
+
 namespace {
+
+constexpr int CODEC = FC_SIM_CODEC;
 
 template <int BITS_RS, int BITS_AG, int NSRC>
 hipError_t launch_sim_src(const uint16_t *x, int64_t n_elems, int group, uint16_t *y, hipStream_t stream)
@@ -152,8 +208,9 @@ hipError_t launch_sim_src(const uint16_t *x, int64_t n_elems, int group, uint16_
     const dim3 grid((unsigned)((n_elems + kSimTileElems - 1) / kSimTileElems)), block(kSimBlockThreads);
     const int lpg = group / kSimLaneElems;
     if (lpg == 8)                                                      // g = 128: the lane pattern is a constant
-        return launch_kernel(k_allreduce_fused<BITS_RS, BITS_AG, NSRC, 8>, grid, block, stream, x, n_elems, lpg, y);
-    return launch_kernel(k_allreduce_fused<BITS_RS, BITS_AG, NSRC, 0>, grid, block, stream, x, n_elems, lpg, y);
+        return launch_kernel(k_allreduce_fused<CODEC, BITS_RS, BITS_AG, NSRC, 8>, grid, block, stream, x, n_elems,
+                             lpg, y);
+    return launch_kernel(k_allreduce_fused<CODEC, BITS_RS, BITS_AG, NSRC, 0>, grid, block, stream, x, n_elems, lpg, y);
 }
 
 template <int BITS_RS, int BITS_AG>
@@ -172,24 +229,49 @@ hipError_t launch_sim_bits(const uint16_t *x, int n_src, int64_t n_elems, int gr
     }
 }
 
-}  // namespace
-
-bool allreduce_fused_applies(int64_t n_elems, int group)
-{
-    // the tile count must fit the 32-bit workgroup index
-    return group <= kSimWaveElems && n_elems / kSimTileElems < 0x7FFFFFFF;
-}
-
-hipError_t launch_allreduce_fused(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
-                                  void *y_f16, hipStream_t stream)
+hipError_t launch_sim_codec(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems, int group,
+                            void *y_f16, hipStream_t stream)
 {
     const uint16_t *x = static_cast<const uint16_t *>(x_f16);
     uint16_t *y = static_cast<uint16_t *>(y_f16);
-    if (bits_rs == 4)
-        return bits_ag == 4 ? launch_sim_bits<4, 4>(x, n_src, n_elems, group, y, stream)
-                            : launch_sim_bits<4, 8>(x, n_src, n_elems, group, y, stream);
-    return bits_ag == 4 ? launch_sim_bits<8, 4>(x, n_src, n_elems, group, y, stream)
-                        : launch_sim_bits<8, 8>(x, n_src, n_elems, group, y, stream);
+    if constexpr (CODEC == kFp8) {
+        return (bits_rs == 8 && bits_ag == 8) ? launch_sim_bits<8, 8>(x, n_src, n_elems, group, y, stream)
+                                              : hipErrorInvalidValue;
+    } else {
+        if (bits_rs == 4)
+            return bits_ag == 4 ? launch_sim_bits<4, 4>(x, n_src, n_elems, group, y, stream)
+                                : launch_sim_bits<4, 8>(x, n_src, n_elems, group, y, stream);
+        return bits_ag == 4 ? launch_sim_bits<8, 4>(x, n_src, n_elems, group, y, stream)
+                            : launch_sim_bits<8, 8>(x, n_src, n_elems, group, y, stream);
+    }
 }
+
+}  // namespace
+
+#if FC_SIM_CODEC == 0
+hipError_t launch_allreduce_fused_asym(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems,
+                                       int group, void *y_f16, hipStream_t stream)
+{
+    return launch_sim_codec(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+}
+#elif FC_SIM_CODEC == 1
+hipError_t launch_allreduce_fused_sym(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems,
+                                      int group, void *y_f16, hipStream_t stream)
+{
+    return launch_sim_codec(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+}
+#elif FC_SIM_CODEC == 2
+hipError_t launch_allreduce_fused_fp8(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems,
+                                      int group, void *y_f16, hipStream_t stream)
+{
+    return launch_sim_codec(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+}
+#else
+hipError_t launch_allreduce_fused_cmeta(int bits_rs, int bits_ag, const void *x_f16, int n_src, int64_t n_elems,
+                                        int group, void *y_f16, hipStream_t stream)
+{
+    return launch_sim_codec(bits_rs, bits_ag, x_f16, n_src, n_elems, group, y_f16, stream);
+}
+#endif
 
 }  // namespace fc

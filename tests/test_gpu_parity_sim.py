@@ -1,7 +1,8 @@
 """GPU parity of the single-kernel all-reduce for bandwidth-bound volumes (fc_allreduce_sim above 2^20 elements per
-partial, groups of at most 1024 elements) against the CPU oracle, bit for bit, and against the three-kernel sequence
-(fc_quantize x N, fc_dequant_reduce_requant, fc_dequantize called one by one through the binding).  Volumes are just
-above the threshold so that the oracle finishes in a fraction of a second per case."""
+partial, its symmetric / FP8 / binary16-metadata counterparts at any volume; groups of at most 1024 elements) against
+the CPU oracle, bit for bit, and against the three-kernel sequence (quantize x N, dequant-reduce-requant, dequantize
+called one by one through the binding).  Volumes are just above the threshold so that the oracle finishes in a
+fraction of a second per case."""
 import numpy as np
 import pytest
 
@@ -138,3 +139,94 @@ def test_under_graph_capture_and_replay(fc):
         graph.replay()
         torch.cuda.synchronize()
         check(y.cpu().numpy(), oracle.allreduce_sim(x, g, 4, 4), "replay %d" % rep)
+
+
+# --------------------------------------------------------------------------- #
+# the other quantizers: symmetric (Eq. 3-4), FP8 E4M3, asymmetric with binary16 metadata
+# --------------------------------------------------------------------------- #
+
+def variant(fc, name):
+    if name == "sym":
+        return (lambda xd, g, bi, bo: fc.allreduce_sim_sym(xd, g, bi, bo)), \
+               (lambda x, g, bi, bo: oracle.allreduce_sim_sym(x, g, bi, bo))
+    if name == "fp8":
+        return (lambda xd, g, bi, bo: fc.allreduce_sim_fp8(xd, g)), (lambda x, g, bi, bo: oracle.allreduce_sim_fp8(x, g))
+    return (lambda xd, g, bi, bo: fc.allreduce_sim_cmeta(xd, g, bi, bo)), \
+           (lambda x, g, bi, bo: oracle.allreduce_sim_cmeta(x, g, bi, bo))
+
+
+def bit_pairs(name):
+    return ((8, 8),) if name == "fp8" else ((4, 4), (8, 8), (4, 8), (8, 4))
+
+
+@pytest.mark.parametrize("name", ["sym", "fp8", "cmeta"])
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_variants_every_fan_in_and_bit_width_pair(fc, name, n_src):
+    gpu, ref = variant(fc, name)
+    x = synth_inputs.make_partials(n_src, 40, 4096, seed=300 + n_src, outlier_frac=0.01)
+    xd = dev16(x)
+    for bi, bo in bit_pairs(name):
+        got = gpu(xd, 128, bi, bo)
+        torch.cuda.synchronize()
+        check(got.cpu().numpy(), ref(x, 128, bi, bo), "%s N=%d %d->%d" % (name, n_src, bi, bo))
+
+
+@pytest.mark.parametrize("name", ["sym", "fp8", "cmeta"])
+@pytest.mark.parametrize("tokens,hidden", [(1, 32), (3, 1056), (7, 2080), (33, 4096 + 1024), (9, 1152)])
+def test_variants_group_sizes_and_ragged_tails(fc, name, tokens, hidden):
+    gpu, ref = variant(fc, name)
+    x = synth_inputs.make_partials(3, tokens, hidden, seed=tokens + hidden, outlier_frac=0.01)
+    xd = dev16(x)
+    for group in (32, 64, 128, 256, 512, 1024):
+        if hidden % group:
+            continue
+        for bi, bo in bit_pairs(name)[:2]:
+            got = gpu(xd, group, bi, bo)
+            torch.cuda.synchronize()
+            check(got.cpu().numpy(), ref(x, group, bi, bo), "%s g=%d %dx%d %d->%d" % (name, group, tokens, hidden, bi, bo))
+
+
+@pytest.mark.parametrize("name", ["sym", "fp8", "cmeta"])
+@pytest.mark.parametrize("kind", range(synth_inputs.STRESS_KINDS))
+def test_variants_corner_reaching_distributions(fc, name, kind):
+    gpu, ref = variant(fc, name)
+    for n_src, group in ((2, 32), (4, 128), (8, 1024)):
+        x = synth_inputs.make_partials_stress(n_src, 12, 8192, kind, seed=11 * kind + n_src)
+        xd = dev16(x)
+        for bi, bo in bit_pairs(name):
+            got = gpu(xd, group, bi, bo)
+            torch.cuda.synchronize()
+            check(got.cpu().numpy(), ref(x, group, bi, bo), "%s kind %d N=%d g=%d %d->%d" % (name, kind, n_src, group, bi, bo))
+
+
+@pytest.mark.parametrize("name", ["sym", "fp8", "cmeta"])
+@pytest.mark.parametrize("group", [32, 128, 512])
+def test_variants_hand_picked_hard_groups(fc, name, group):
+    gpu, ref = variant(fc, name)
+    rows = synth_inputs.adversarial_groups(group, seed=group + 1)
+    base = np.tile(rows, (3, 1))
+    x = np.stack([np.roll(base, j, axis=0) if j % 2 == 0 else np.roll(base[:, ::-1].copy(), j, axis=0)
+                  for j in range(4)])
+    xd = dev16(x)
+    for bi, bo in bit_pairs(name):
+        got = gpu(xd, group, bi, bo)
+        torch.cuda.synchronize()
+        check(got.cpu().numpy(), ref(x, group, bi, bo), "%s hard groups g=%d %d->%d" % (name, group, bi, bo))
+
+
+def test_variants_identical_to_their_three_kernel_sequences(fc):
+    n, t, h, g = 4, 24, 8192, 128
+    x = synth_inputs.make_partials(n, t, h, seed=77, outlier_frac=0.01)
+    xd = dev16(x)
+    # symmetric
+    parts = [fc.quantize_sym(xd[j], g, 4) for j in range(n)]
+    co, so = fc.dequant_reduce_requant_sym(torch.stack([p[0] for p in parts]), torch.stack([p[1] for p in parts]), h, g, 4, 8)
+    check(fc.allreduce_sim_sym(xd, g, 4, 8).cpu().numpy(), fc.dequantize_sym(co, so, h, g, 8).cpu().numpy(), "sym")
+    # FP8
+    parts = [fc.quantize_fp8(xd[j], g) for j in range(n)]
+    co, so = fc.dequant_reduce_requant_fp8(torch.stack([p[0] for p in parts]), torch.stack([p[1] for p in parts]), h, g)
+    check(fc.allreduce_sim_fp8(xd, g).cpu().numpy(), fc.dequantize_fp8(co, so, h, g).cpu().numpy(), "fp8")
+    # binary16 metadata
+    parts = [fc.quantize_cmeta(xd[j], g, 8) for j in range(n)]
+    co, mo = fc.dequant_reduce_requant_cmeta(torch.stack([p[0] for p in parts]), torch.stack([p[1] for p in parts]), h, g, 8, 4)
+    check(fc.allreduce_sim_cmeta(xd, g, 8, 4).cpu().numpy(), fc.dequantize_cmeta(co, mo, h, g, 4).cpu().numpy(), "cmeta")
