@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.fc_ref_dequant_reduce_requant_fp8.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, vp, vp]
         L.fc_ref_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp]
         L.fc_ref_hadamard_f32.argtypes = [vp, i64]
+        L.fc_ref_hadamard_blocks_f32.argtypes = [vp, i64]
         L.fc_ref_quantize_rot.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
         L.fc_ref_dequantize_rot.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp]
         L.fc_ref_allreduce_sim_rot.argtypes = [vp, i32, i64, i64, i32, i32, i32, i32, vp]
@@ -99,7 +100,7 @@ def lib() -> ctypes.CDLL:
                      "fc_ref_dequantize_cmeta", "fc_ref_dequant_reduce_cmeta_f32",
                      "fc_ref_dequant_reduce_requant_cmeta", "fc_ref_allreduce_sim_cmeta"):
             getattr(L, name).restype = i32
-        for name in ("fc_ref_hadamard_f32", "fc_ref_quantize_rot", "fc_ref_dequantize_rot",
+        for name in ("fc_ref_hadamard_f32", "fc_ref_hadamard_blocks_f32", "fc_ref_quantize_rot", "fc_ref_dequantize_rot",
                      "fc_ref_allreduce_sim_rot"):
             getattr(L, name).restype = i32
         for name in ("fc_ref_quantize_fp8_f32", "fc_ref_quantize_fp8", "fc_ref_dequantize_fp8_f32",
@@ -424,6 +425,19 @@ def hadamard_f32(x):
     for r in range(flat.shape[0]):
         row = np.ascontiguousarray(flat[r])
         _chk(lib().fc_ref_hadamard_f32(_p(row), n), "hadamard_f32")
+        flat[r] = row
+    return flat.reshape(x.shape)
+
+
+def hadamard_blocks_f32(x):
+    """the transform the rotated entry points apply to a row of any length: hadamard_f32 over every aligned
+    block of B elements of the last axis, B the largest power of two dividing its length."""
+    x = np.array(x, dtype=np.float32, order="C")
+    n = x.shape[-1]
+    flat = x.reshape(-1, n)
+    for r in range(flat.shape[0]):
+        row = np.ascontiguousarray(flat[r])
+        _chk(lib().fc_ref_hadamard_blocks_f32(_p(row), n), "hadamard_blocks_f32")
         flat[r] = row
     return flat.reshape(x.shape)
 

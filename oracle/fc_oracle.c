@@ -75,7 +75,14 @@
  *       group quantizers are invariant);
  *   H4  the rotated values go into the quantizer in fp32 (no rounding to
  *       binary16 in between); the result is binary16(RNE) of the inverse transform
- *       of the dequantized fp32 values.
+ *       of the dequantized fp32 values;
+ *   H5  a hidden dimension that is not a power of two (the rotation table's
+ *       LLaMA-2-13B row: 5120) is rotated block by block: the transform of H1-H3
+ *       over every aligned run of B elements, B the largest power of two that
+ *       divides hidden (5120 = 5 x 1024), i.e. the orthogonal matrix
+ *       I (x) H_B.  A quantization group that is a power of two dividing hidden
+ *       divides B, so it lies inside one block.  For a power of two B = hidden
+ *       and nothing changes.
  * Compact metadata variant (the paper never says how a group's scale and
  * zero-point are stored or sent; this is the asymmetric quantizer of Eq. 1-2 with
  * both kept in binary16, 4 bytes per group instead of 8): the fc_ref_*_cmeta
@@ -759,6 +766,20 @@ int fc_ref_hadamard_f32(float *x, int64_t n)
     return FC_REF_OK;
 }
 
+/* H5: the largest power of two that divides n, and the transform applied to every aligned block of that length */
+static int64_t rotation_block(int64_t n) { return n & -n; }
+
+int fc_ref_hadamard_blocks_f32(float *x, int64_t n)
+{
+    if (n < 1 || !x) return FC_REF_BAD_ARG;
+    const int64_t b = rotation_block(n);
+    for (int64_t at = 0; at < n; at += b) {
+        const int rc = fc_ref_hadamard_f32(x + at, b);
+        if (rc != FC_REF_OK) return rc;
+    }
+    return FC_REF_OK;
+}
+
 static int quantize_any_f32(int quantizer, const float *x, int64_t tokens, int64_t hidden, int group,
                             int bits, uint8_t *codes, float *scales, float *zeros)
 {
@@ -781,8 +802,8 @@ static int dequantize_any_f32(int quantizer, const uint8_t *codes, const float *
 int fc_ref_quantize_rot(const uint16_t *x_f16, int64_t tokens, int64_t hidden, int group, int bits,
                         int quantizer, uint8_t *codes, float *scales, float *zeros)
 {
-    const int n = log2_exact(hidden);
-    if (!check_shape(tokens, hidden, group, bits) || n < 0) return FC_REF_BAD_ARG;
+    if (hidden < 1 || !check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    const int n = log2_exact(rotation_block(hidden));         /* H5: per block of 2^n elements */
     if (tokens == 0) return FC_REF_OK;
     if (!x_f16 || !codes || !scales) return FC_REF_BAD_ARG;
     float *xf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
@@ -791,7 +812,7 @@ int fc_ref_quantize_rot(const uint16_t *x_f16, int64_t tokens, int64_t hidden, i
     for (int64_t t = 0; t < tokens; ++t) {
         float *row = xf + t * hidden;
         for (int64_t h = 0; h < hidden; ++h) row[h] = fc_ref_half_to_float(x_f16[t * hidden + h]);
-        fc_ref_hadamard_f32(row, hidden);
+        fc_ref_hadamard_blocks_f32(row, hidden);
         for (int64_t h = 0; h < hidden; ++h) row[h] *= fwd;
     }
     const int rc = quantize_any_f32(quantizer, xf, tokens, hidden, group, bits, codes, scales, zeros);
@@ -804,8 +825,8 @@ int fc_ref_dequantize_rot(const uint8_t *codes, const float *scales, const float
                           int64_t tokens, int64_t hidden, int group, int bits, int quantizer,
                           uint16_t *y_f16)
 {
-    const int n = log2_exact(hidden);
-    if (!check_shape(tokens, hidden, group, bits) || n < 0) return FC_REF_BAD_ARG;
+    if (hidden < 1 || !check_shape(tokens, hidden, group, bits)) return FC_REF_BAD_ARG;
+    const int n = log2_exact(rotation_block(hidden));         /* H5: per block of 2^n elements */
     if (tokens == 0) return FC_REF_OK;
     if (!codes || !scales || !y_f16) return FC_REF_BAD_ARG;
     float *yf = (float *)malloc(sizeof(float) * (size_t)(tokens * hidden));
@@ -814,7 +835,7 @@ int fc_ref_dequantize_rot(const uint8_t *codes, const float *scales, const float
     const float inv = ldexpf(1.0f, -(n / 2));                /* 2^-floor(n/2) */
     for (int64_t t = 0; rc == FC_REF_OK && t < tokens; ++t) {
         float *row = yf + t * hidden;
-        fc_ref_hadamard_f32(row, hidden);
+        fc_ref_hadamard_blocks_f32(row, hidden);
         for (int64_t h = 0; h < hidden; ++h) y_f16[t * hidden + h] = fc_ref_float_to_half(row[h] * inv);
     }
     free(yf);
@@ -827,7 +848,7 @@ int fc_ref_allreduce_sim_rot(const uint16_t *x_f16, int n_src, int64_t tokens, i
                              int group, int bits_rs, int bits_ag, int quantizer, uint16_t *y_f16)
 {
     if (!check_shape(tokens, hidden, group, bits_rs) || !check_shape(tokens, hidden, group, bits_ag)
-        || n_src < 1 || log2_exact(hidden) < 0)
+        || n_src < 1 || hidden < 1)
         return FC_REF_BAD_ARG;
     if (tokens == 0) return FC_REF_OK;
     const int64_t m = tokens * hidden, ng = m / group;

@@ -166,7 +166,64 @@ def test_rotated_allreduce_error_bound_and_gain_on_outlier_channels(bits):
 
 def test_rot_bad_arguments():
     x = synth_inputs.make_partials(1, 2, 96, seed=1)[0]
+    oracle.quantize_rot(x, 32, 8)                        # hidden 96 = 3 x 32: rotated block by block
     with pytest.raises(Exception):
-        oracle.quantize_rot(x, 32, 8)                    # hidden not a power of two
+        oracle.quantize_rot(x, 64, 8)                    # the group does not divide hidden
     with pytest.raises(Exception):
         oracle.quantize_rot(synth_inputs.make_partials(1, 2, 128, seed=1)[0], 32, 4, oracle.FP8)
+
+
+# --------------------------------------------------------------------------- #
+# rows whose length is not a power of two: the transform block by block (I (x) H_B, B the largest power of two
+# dividing the length; the rotation table's LLaMA-2-13B row has hidden 5120 = 5 x 1024)
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("n,block", [(1, 1), (6, 2), (12, 4), (96, 32), (640, 128), (5120, 1024), (3072, 1024),
+                                     (7168, 1024), (6144, 2048), (4096, 4096), (17, 1)])
+def test_block_transform_is_the_kronecker_product_on_integers(n, block):
+    rng = np.random.default_rng(n)
+    x = rng.integers(-50, 51, size=(2, n))
+    hb = scipy.linalg.hadamard(block).astype(np.int64) if block > 1 else np.ones((1, 1), np.int64)
+    want = (x.reshape(2, n // block, block) @ hb).reshape(2, n)       # == x @ kron(I, H_B)
+    got = oracle.hadamard_blocks_f32(x.astype(np.float32))
+    assert np.array_equal(got.astype(np.int64), want)
+    assert np.array_equal(oracle.hadamard_blocks_f32(got).astype(np.int64), block * x)     # involution up to B
+    if n <= 640:                                                        # the dense orthogonal matrix itself
+        dense = scipy.linalg.block_diag(*([hb] * (n // block)))
+        assert np.array_equal(want, x @ dense)
+        assert np.array_equal(dense @ dense.T, block * np.eye(n, dtype=np.int64))
+    if block == n:                                                      # a power of two: the plain transform
+        assert np.array_equal(bits_of(got), bits_of(oracle.hadamard_f32(x.astype(np.float32))))
+
+
+@pytest.mark.parametrize("quantizer,bits", [(oracle.ASYM, 4), (oracle.ASYM, 8), (oracle.SYM, 4), (oracle.FP8, 8)])
+@pytest.mark.parametrize("hidden,block", [(5120, 1024), (3072, 1024), (6144, 2048), (96, 32)])
+def test_rotated_quantization_of_a_row_is_that_of_its_blocks(quantizer, bits, hidden, block):
+    # blocks are independent and groups lie inside blocks: quantizing [tokens, hidden] must equal quantizing the
+    # same memory viewed as [tokens * hidden / B, B], whose rows are powers of two (the case pinned above and by
+    # the hand examples); likewise for Dequantize and for the whole all-reduce
+    rng = np.random.default_rng(hidden + bits)
+    tokens, n_src = 3, 2
+    x = (rng.standard_normal((n_src, tokens, hidden)) * np.where(rng.random(hidden) < 0.02, 20.0, 1.0)).astype(np.float16)
+    xb = x.reshape(n_src, tokens * hidden // block, block)
+    for group in (32, block):
+        c, s, z = oracle.quantize_rot(x[0], group, bits, quantizer)
+        cb, sb, zb = oracle.quantize_rot(xb[0], group, bits, quantizer)
+        assert c.tobytes() == cb.tobytes() and bits_of(s).tobytes() == bits_of(sb).tobytes()
+        if quantizer == oracle.ASYM:
+            assert bits_of(z).tobytes() == bits_of(zb).tobytes()
+        y = oracle.dequantize_rot(c, s, z, hidden, group, bits, quantizer)
+        yb = oracle.dequantize_rot(cb, sb, zb, block, group, bits, quantizer)
+        assert y.view(np.uint16).tobytes() == yb.view(np.uint16).tobytes()
+        a = oracle.allreduce_sim_rot(x, group, bits, bits, quantizer)
+        ab = oracle.allreduce_sim_rot(xb, group, bits, bits, quantizer)
+        assert a.view(np.uint16).tobytes() == ab.view(np.uint16).tobytes()
+
+
+def test_block_rotation_spreads_outlier_channels_within_blocks():
+    # what the rotation is for (Section 4): with outlier channels the coarse-group error drops by a large factor
+    x = synth_inputs.make_partials(4, 8, 5120, seed=5, outlier_frac=0.01)
+    exact = x.astype(np.float64).sum(0)
+    plain = oracle.allreduce_sim(x, 1024, 4, 4).astype(np.float64)
+    rot = oracle.allreduce_sim_rot(x, 1024, 4, 4, oracle.ASYM).astype(np.float64)
+    assert ((rot - exact) ** 2).mean() * 3 < ((plain - exact) ** 2).mean()
