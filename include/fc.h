@@ -267,13 +267,16 @@ FC_API int fc_allreduce_sim_cmeta(const void *x_f16, int n_src, int64_t tokens, 
  * the first quantization; the rotation is linear, so the unchanged
  * fc_dequant_reduce_requant* step sums rotated partials; the inverse rotation follows the
  * last Dequantize.  `quantizer` selects the code (FC_QUANTIZER_*; FP8 needs bits == 8;
- * zeros may be NULL unless FC_QUANTIZER_ASYM).  hidden must be 2048, 4096 or 8192; other
- * rules as above.  Results are bit-identical to:
- *     r = WHT(x) * 2^-ceil(n/2),  n = log2(hidden)      (fc_quantize_rot, then the quantizer on r in fp32)
- *     y = binary16(WHT(x^) * 2^-floor(n/2))              (fc_dequantize_rot on the dequantized fp32 x^)
- * where WHT is the natural-order Walsh-Hadamard transform over the hidden dimension of one
- * token, evaluated in fp32 as butterfly stages (a, b) -> (a + b, a - b) with spans
- * 1, 2, 4, ..., hidden/2 in that order.
+ * zeros may be NULL unless FC_QUANTIZER_ASYM).  The transform runs over every aligned block of
+ * B elements of a token's row, B the largest power of two that divides hidden: the whole row when
+ * hidden is a power of two, five blocks of 1024 for hidden 5120 (the rotation table's LLaMA-2-13B
+ * row; the paper names no transform for such a length).  B must be 1024, 2048, 4096 or 8192
+ * (FC_ERR_SHAPE otherwise); every group, a power of two dividing hidden, lies inside one block.
+ * Other rules as above.  Results are bit-identical to:
+ *     r = WHT_B(x) * 2^-ceil(n/2),  n = log2(B)          (fc_quantize_rot, then the quantizer on r in fp32)
+ *     y = binary16(WHT_B(x^) * 2^-floor(n/2))            (fc_dequantize_rot on the dequantized fp32 x^)
+ * where WHT_B applies, to each block, the natural-order Walsh-Hadamard transform evaluated in
+ * fp32 as butterfly stages (a, b) -> (a + b, a - b) with spans 1, 2, 4, ..., B/2 in that order.
  */
 #define FC_QUANTIZER_ASYM 0   /* Eq. 1-2 */
 #define FC_QUANTIZER_SYM 1    /* Eq. 3-4 */

@@ -56,7 +56,8 @@ def sweep(x, groups, precisions=PRECISIONS, rotation=False):
         mse = float((err * err).mean())
         rows.append({"precision": "FP8", "quantizer": "sym", "group": g, "mse": mse,
                      "snr_db": float(10.0 * torch.log10(torch.tensor(power / mse))) if mse > 0 else float("inf")})
-    if rotation and x.shape[2] in (2048, 4096, 8192):  # the "w/ HT" columns of the rotation table
+    block = x.shape[2] & -x.shape[2]                   # the rotation runs over blocks of this many elements
+    if rotation and block in (1024, 2048, 4096, 8192):  # the "w/ HT" columns of the rotation table
         for label, b_rs, b_ag, qz in [(l, p[0], p[1], q) for l, p in precisions.items()
                                       for q in (fc.QUANTIZER_ASYM, fc.QUANTIZER_SYM)] + \
                                      [("FP8", 8, 8, fc.QUANTIZER_FP8)]:

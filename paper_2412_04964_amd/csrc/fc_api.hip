@@ -238,7 +238,13 @@ int static_scratch(void **ptr)
     return FC_OK;
 }
 
-bool rot_hidden_ok(int64_t hidden) { return hidden == 2048 || hidden == 4096 || hidden == 8192; }
+// the rotation runs over aligned blocks of the largest power of two dividing hidden
+bool rot_hidden_ok(int64_t hidden)
+{
+    if (hidden <= 0 || hidden > 0x7FFFFFFF) return false;
+    const int b = fc::rotation_block(hidden);
+    return b == 1024 || b == 2048 || b == 4096 || b == 8192;
+}
 
 int check_quantizer(int quantizer, int bits)
 {

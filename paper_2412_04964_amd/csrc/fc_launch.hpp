@@ -75,7 +75,9 @@ hipError_t launch_quantize_wide(int bits, int codec, const void *x_f16, int64_t 
                                 void *codes, float *scales, float *zeros, hipStream_t stream);
 hipError_t launch_fused_wide(int bits_in, int bits_out, const FusedArgs &a, hipStream_t stream);
 
-// Hadamard rotation fused into the quantizer / dequantizer (fc_rot.hip): hidden in {2048, 4096, 8192}.
+// Hadamard rotation fused into the quantizer / dequantizer (fc_rot.hip), applied to every aligned block of
+// rotation_block(hidden) elements, which must be 1024, 2048, 4096 or 8192.
+inline int rotation_block(int64_t hidden) { return (int)(hidden & -hidden); }     // largest power of two dividing hidden
 hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t tokens, int hidden, int group,
                                void *codes, float *scales, float *zeros, hipStream_t stream);
 hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,

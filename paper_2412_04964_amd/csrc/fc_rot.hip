@@ -10,7 +10,11 @@
 // computes it, so any assignment of butterflies to threads that keeps the stage
 // order is bit-identical.
 //
-// One workgroup owns one token row (hidden = 2048, 4096 or 8192) and keeps it
+// The transform runs over aligned blocks of B = 2^LB elements, B the largest power of two dividing hidden (the
+// whole row when hidden is a power of two; 5 x 1024 for hidden 5120).  Blocks and quantization groups never cross
+// block boundaries, so the tensor is handled as a flat sequence of chunks of 2^LOGH elements (LOGH = LB, except
+// that 1024-element blocks go two to a chunk of 2048).
+// One workgroup owns one chunk (2048, 4096 or 8192 elements) and keeps it
 // in registers, R = 16 or 32 values per thread.  The stages over the bits of
 // the index that live inside a thread run in registers; then the row goes to
 // LDS and each further phase gives every thread the R values that differ in
@@ -79,15 +83,15 @@ __device__ __forceinline__ void lds_phase(float *row, u32 tid)
     for (int q = 0; q < R; ++q) base[at(q)] = x[q];
 }
 
-// Remaining stages for index bits [B0, LOGH), R registers per thread, in phases of up to log2(R) bits.
-template <int B0, int LOGH, int R, int LT, int LE>
+// Remaining stages for index bits [B0, END), R registers per thread, in phases of up to log2(R) bits.
+template <int B0, int END, int R, int LT, int LE>
 __device__ __forceinline__ void lds_phases(float *row, u32 tid)
 {
-    if constexpr (B0 < LOGH) {
-        constexpr int NB = (LOGH - B0) < ilog2(R) ? (LOGH - B0) : ilog2(R);
+    if constexpr (B0 < END) {
+        constexpr int NB = (END - B0) < ilog2(R) ? (END - B0) : ilog2(R);
         lds_phase<B0, NB, R, LT, LE>(row, tid);
         __syncthreads();
-        lds_phases<B0 + NB, LOGH, R, LT, LE>(row, tid);
+        lds_phases<B0 + NB, END, R, LT, LE>(row, tid);
     }
 }
 
@@ -106,13 +110,14 @@ struct RowShape {
     static_assert(T >= 64 && (P == 1 || P == 2), "rows of 2048 to 8192 elements");
 };
 
-// In-place transform of the row held as v[p][i] = element (p*T + tid)*EPL + i.  With S0 = 1 the caller has
-// already applied the first stage (span 1).
-template <int BITS, int LOGH, int S0, int NP, int NE>
+// In-place transform of every aligned block of 2^LB elements of the chunk held as
+// v[p][i] = element (p*T + tid)*EPL + i.  With S0 = 1 the caller has already applied the first stage (span 1).
+template <int BITS, int LOGH, int LB, int S0, int NP, int NE>
 __device__ __forceinline__ void hadamard_row(float (&v)[NP][NE], float *row, u32 tid)
 {
     using S = RowShape<BITS, LOGH>;
     static_assert(NP == S::P && NE == S::EPL, "row held as v[P][EPL]");
+    static_assert(LB <= LOGH && LB > S::LE, "blocks of at least two lanes, at most the chunk");
 #pragma unroll
     for (int p = 0; p < S::P; ++p) butterflies<S::EPL, S::LE, S0>(v[p]);
 #pragma unroll
@@ -124,7 +129,7 @@ __device__ __forceinline__ void hadamard_row(float (&v)[NP][NE], float *row, u32
                            __builtin_bit_cast(u32, v[p][4 * k + 2]), __builtin_bit_cast(u32, v[p][4 * k + 3])};
     }
     __syncthreads();
-    lds_phases<S::LE, LOGH, S::R, S::LT, S::LE>(row, tid);     // ends with a barrier
+    lds_phases<S::LE, LB, S::R, S::LT, S::LE>(row, tid);       // ends with a barrier
 #pragma unroll
     for (int p = 0; p < S::P; ++p) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(row + padded<S::LE>((p * S::T + tid) * S::EPL));
@@ -140,10 +145,12 @@ __device__ __forceinline__ void hadamard_row(float (&v)[NP][NE], float *row, u32
     }
 }
 
-// Rotate one token row and quantize it (FinegrainedQuantize of Algorithm 1 on the rotated values).
-template <int BITS, int CODEC, int LOGH>
+// Rotate one chunk block by block and quantize it (FinegrainedQuantize of Algorithm 1 on the rotated values).
+// n_elems: elements of the whole tensor (a multiple of 2^LB; the last chunk may be a partial one when LB < LOGH:
+// lanes beyond the end read zeros and have their stores dropped or skipped).
+template <int BITS, int CODEC, int LOGH, int LB>
 __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
-    const uint16_t *__restrict__ x, int lpg, int group_shift, uint8_t *__restrict__ codes,
+    const uint16_t *__restrict__ x, int64_t n_elems, int lpg, int group_shift, uint8_t *__restrict__ codes,
     float *__restrict__ scales, float *__restrict__ zeros)
 {
     using S = RowShape<BITS, LOGH>;
@@ -161,8 +168,9 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t e0 = (int64_t)blockIdx.x << LOGH;
-    const rsrc_t rx = make_rsrc(x + e0, (int64_t)S::H * 2);
-    const rsrc_t rc = make_rsrc(codes + e0 * BITS / 8, (int64_t)S::H * BITS / 8);
+    const int64_t here = (n_elems - e0) < (int64_t)S::H ? (n_elems - e0) : (int64_t)S::H;      // elements of this chunk
+    const rsrc_t rx = make_rsrc(x + e0, here * 2);
+    const rsrc_t rc = make_rsrc(codes + e0 * BITS / 8, here * BITS / 8);
 
 #pragma unroll
     for (int p = 0; p < P; ++p)
@@ -184,14 +192,14 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
     }
     __syncthreads();                                   // the image is read; its LDS becomes the row
 
-    hadamard_row<BITS, LOGH, 1>(v, row, tid);
-    // Forward scaling fwd = 2^-ceil(n/2).  It is a power of two and nothing here is near the ends of
+    hadamard_row<BITS, LOGH, LB, 1>(v, row, tid);
+    // Forward scaling fwd = 2^-ceil(n/2), n = LB.  It is a power of two and nothing here is near the ends of
     // the fp32 range (the transformed values are multiples of 2^-24 below 2^30), so scaling commutes
     // with every rounding: instead of scaling all values, the group's min and max are scaled (which
     // gives the scale, reciprocal and zero-point of the scaled values exactly) and the codes are formed
     // from the unscaled values with the reciprocal times fwd, the same real product and hence the
     // same rounded one.
-    constexpr float fwd = 1.0f / (float)(1 << ((LOGH + 1) / 2));
+    constexpr float fwd = 1.0f / (float)(1 << ((LB + 1) / 2));
 
     // group min / max: inside the wavefront, then across the wavefronts of the sub-tile, then
     // (one group per row of two sub-tiles) across the sub-tiles
@@ -226,7 +234,7 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{word[0], word[1], word[2], word[3]}, rc,
                                                (p * T + tid) * 16, 0, kStreamStorePolicy);
         const u32 lane_in_row = p * T + tid;
-        if ((lane_in_row & (u32)(lpg - 1)) == 0) {
+        if ((lane_in_row & (u32)(lpg - 1)) == 0 && (int64_t)(lane_in_row * EPL) < here) {
             const int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
             scales[gi] = s;
             if constexpr (CODEC == kAsym) zeros[gi] = zf;
@@ -234,11 +242,11 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_quantize_rot(
     }
 }
 
-// Dequantize one token row, rotate it back and round to binary16 (last step of Algorithm 1).
-template <int BITS, int CODEC, int LOGH>
+// Dequantize one chunk, rotate it back block by block and round to binary16 (last step of Algorithm 1).
+template <int BITS, int CODEC, int LOGH, int LB>
 __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
     const uint8_t *__restrict__ codes, const float *__restrict__ scales, const float *__restrict__ zeros,
-    int group_shift, uint16_t *__restrict__ y)
+    int64_t n_elems, int group_shift, uint16_t *__restrict__ y)
 {
     using S = RowShape<BITS, LOGH>;
     constexpr int EPL = S::EPL, T = S::T, P = S::P;
@@ -253,14 +261,17 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t e0 = (int64_t)blockIdx.x << LOGH;
     const int64_t g_row = e0 >> group_shift;
-    const rsrc_t rc = make_rsrc(codes + e0 * BITS / 8, (int64_t)S::H * BITS / 8);
-    const rsrc_t ry = make_rsrc(y + e0, (int64_t)S::H * 2);
+    const int64_t here = (n_elems - e0) < (int64_t)S::H ? (n_elems - e0) : (int64_t)S::H;      // elements of this chunk
+    const int64_t g_last = (n_elems >> group_shift) - 1;
+    const rsrc_t rc = make_rsrc(codes + e0 * BITS / 8, here * BITS / 8);
+    const rsrc_t ry = make_rsrc(y + e0, here * 2);
 
     float v[P][EPL];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const u32 lane_in_row = p * T + tid;
-        const int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
+        int64_t gi = g_row + ((lane_in_row * EPL) >> group_shift);
+        gi = gi < g_last ? gi : g_last;                    // lanes beyond a partial last chunk stay inside the arrays
         const float s = scales[gi];
         const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rc, lane_in_row * 16, 0, kStreamLoadPolicy);
         if constexpr (CODEC == kFp8) {
@@ -287,9 +298,9 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
         }
     }
 
-    hadamard_row<BITS, LOGH, 0>(v, row, tid);
+    hadamard_row<BITS, LOGH, LB, 0>(v, row, tid);
     __syncthreads();                                   // the row is read; its LDS becomes the output image
-    constexpr float inv = 1.0f / (float)(1 << (LOGH / 2));             // 2^-floor(n/2)
+    constexpr float inv = 1.0f / (float)(1 << (LB / 2));               // 2^-floor(n/2), n = LB
 
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -316,46 +327,51 @@ __global__ __launch_bounds__((RowShape<BITS, LOGH>::T)) void k_dequantize_rot(
 }
 
 // ---------------------------------------------------------------------------
-// launchers: hidden in {2048, 4096, 8192}, group a power of two in [32, hidden]
+// launchers: block = largest power of two dividing hidden, in {1024, 2048, 4096, 8192};
+// group a power of two in [32, block]
 // ---------------------------------------------------------------------------
 namespace {
 
-template <int BITS, int CODEC, int LOGH>
-hipError_t quantize_rot_one(const uint16_t *x, int64_t tokens, int group, uint8_t *c, float *scales,
+template <int BITS, int CODEC, int LOGH, int LB>
+hipError_t quantize_rot_one(const uint16_t *x, int64_t n_elems, int group, uint8_t *c, float *scales,
                             float *zeros, hipStream_t stream)
 {
-    return launch_kernel(k_quantize_rot<BITS, CODEC, LOGH>, dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T),
-                         stream, x, group / lane_elems(BITS), log2_int(group), c, scales, zeros);
+    const unsigned grid = (unsigned)((n_elems + ((int64_t)1 << LOGH) - 1) >> LOGH);
+    return launch_kernel(k_quantize_rot<BITS, CODEC, LOGH, LB>, dim3(grid), dim3(RowShape<BITS, LOGH>::T), stream, x,
+                         n_elems, group / lane_elems(BITS), log2_int(group), c, scales, zeros);
 }
 
 template <int BITS, int CODEC>
-hipError_t quantize_rot_h(int log_h, const uint16_t *x, int64_t tokens, int group, uint8_t *c, float *scales,
+hipError_t quantize_rot_h(int log_b, const uint16_t *x, int64_t n_elems, int group, uint8_t *c, float *scales,
                           float *zeros, hipStream_t stream)
 {
-    switch (log_h) {
-    case 11: return quantize_rot_one<BITS, CODEC, 11>(x, tokens, group, c, scales, zeros, stream);
-    case 12: return quantize_rot_one<BITS, CODEC, 12>(x, tokens, group, c, scales, zeros, stream);
-    case 13: return quantize_rot_one<BITS, CODEC, 13>(x, tokens, group, c, scales, zeros, stream);
+    switch (log_b) {
+    case 10: return quantize_rot_one<BITS, CODEC, 11, 10>(x, n_elems, group, c, scales, zeros, stream);
+    case 11: return quantize_rot_one<BITS, CODEC, 11, 11>(x, n_elems, group, c, scales, zeros, stream);
+    case 12: return quantize_rot_one<BITS, CODEC, 12, 12>(x, n_elems, group, c, scales, zeros, stream);
+    case 13: return quantize_rot_one<BITS, CODEC, 13, 13>(x, n_elems, group, c, scales, zeros, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
-template <int BITS, int CODEC, int LOGH>
-hipError_t dequantize_rot_one(const uint8_t *c, const float *scales, const float *zeros, int64_t tokens,
+template <int BITS, int CODEC, int LOGH, int LB>
+hipError_t dequantize_rot_one(const uint8_t *c, const float *scales, const float *zeros, int64_t n_elems,
                               int group, uint16_t *y, hipStream_t stream)
 {
-    return launch_kernel(k_dequantize_rot<BITS, CODEC, LOGH>, dim3((unsigned)tokens), dim3(RowShape<BITS, LOGH>::T),
-                         stream, c, scales, zeros, log2_int(group), y);
+    const unsigned grid = (unsigned)((n_elems + ((int64_t)1 << LOGH) - 1) >> LOGH);
+    return launch_kernel(k_dequantize_rot<BITS, CODEC, LOGH, LB>, dim3(grid), dim3(RowShape<BITS, LOGH>::T), stream, c,
+                         scales, zeros, n_elems, log2_int(group), y);
 }
 
 template <int BITS, int CODEC>
-hipError_t dequantize_rot_h(int log_h, const uint8_t *c, const float *scales, const float *zeros,
-                            int64_t tokens, int group, uint16_t *y, hipStream_t stream)
+hipError_t dequantize_rot_h(int log_b, const uint8_t *c, const float *scales, const float *zeros,
+                            int64_t n_elems, int group, uint16_t *y, hipStream_t stream)
 {
-    switch (log_h) {
-    case 11: return dequantize_rot_one<BITS, CODEC, 11>(c, scales, zeros, tokens, group, y, stream);
-    case 12: return dequantize_rot_one<BITS, CODEC, 12>(c, scales, zeros, tokens, group, y, stream);
-    case 13: return dequantize_rot_one<BITS, CODEC, 13>(c, scales, zeros, tokens, group, y, stream);
+    switch (log_b) {
+    case 10: return dequantize_rot_one<BITS, CODEC, 11, 10>(c, scales, zeros, n_elems, group, y, stream);
+    case 11: return dequantize_rot_one<BITS, CODEC, 11, 11>(c, scales, zeros, n_elems, group, y, stream);
+    case 12: return dequantize_rot_one<BITS, CODEC, 12, 12>(c, scales, zeros, n_elems, group, y, stream);
+    case 13: return dequantize_rot_one<BITS, CODEC, 13, 13>(c, scales, zeros, n_elems, group, y, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -367,15 +383,16 @@ hipError_t launch_quantize_rot(int bits, int codec, const void *x_f16, int64_t t
 {
     const uint16_t *x = static_cast<const uint16_t *>(x_f16);
     uint8_t *c = static_cast<uint8_t *>(codes);
-    const int lh = log2_int(hidden);
+    const int lb = log2_int(rotation_block(hidden));
+    const int64_t n = tokens * hidden;
     if (codec == CODEC_FP8)
-        return bits == 8 ? quantize_rot_h<8, kFp8>(lh, x, tokens, group, c, scales, nullptr, stream)
+        return bits == 8 ? quantize_rot_h<8, kFp8>(lb, x, n, group, c, scales, nullptr, stream)
                          : hipErrorInvalidValue;
     if (bits == 4)
-        return codec == CODEC_ASYM ? quantize_rot_h<4, kAsym>(lh, x, tokens, group, c, scales, zeros, stream)
-                                   : quantize_rot_h<4, kSym>(lh, x, tokens, group, c, scales, nullptr, stream);
-    return codec == CODEC_ASYM ? quantize_rot_h<8, kAsym>(lh, x, tokens, group, c, scales, zeros, stream)
-                               : quantize_rot_h<8, kSym>(lh, x, tokens, group, c, scales, nullptr, stream);
+        return codec == CODEC_ASYM ? quantize_rot_h<4, kAsym>(lb, x, n, group, c, scales, zeros, stream)
+                                   : quantize_rot_h<4, kSym>(lb, x, n, group, c, scales, nullptr, stream);
+    return codec == CODEC_ASYM ? quantize_rot_h<8, kAsym>(lb, x, n, group, c, scales, zeros, stream)
+                               : quantize_rot_h<8, kSym>(lb, x, n, group, c, scales, nullptr, stream);
 }
 
 hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const float *scales, const float *zeros,
@@ -383,15 +400,16 @@ hipError_t launch_dequantize_rot(int bits, int codec, const void *codes, const f
 {
     const uint8_t *c = static_cast<const uint8_t *>(codes);
     uint16_t *y = static_cast<uint16_t *>(y_f16);
-    const int lh = log2_int(hidden);
+    const int lb = log2_int(rotation_block(hidden));
+    const int64_t n = tokens * hidden;
     if (codec == CODEC_FP8)
-        return bits == 8 ? dequantize_rot_h<8, kFp8>(lh, c, scales, nullptr, tokens, group, y, stream)
+        return bits == 8 ? dequantize_rot_h<8, kFp8>(lb, c, scales, nullptr, n, group, y, stream)
                          : hipErrorInvalidValue;
     if (bits == 4)
-        return codec == CODEC_ASYM ? dequantize_rot_h<4, kAsym>(lh, c, scales, zeros, tokens, group, y, stream)
-                                   : dequantize_rot_h<4, kSym>(lh, c, scales, nullptr, tokens, group, y, stream);
-    return codec == CODEC_ASYM ? dequantize_rot_h<8, kAsym>(lh, c, scales, zeros, tokens, group, y, stream)
-                               : dequantize_rot_h<8, kSym>(lh, c, scales, nullptr, tokens, group, y, stream);
+        return codec == CODEC_ASYM ? dequantize_rot_h<4, kAsym>(lb, c, scales, zeros, n, group, y, stream)
+                                   : dequantize_rot_h<4, kSym>(lb, c, scales, nullptr, n, group, y, stream);
+    return codec == CODEC_ASYM ? dequantize_rot_h<8, kAsym>(lb, c, scales, zeros, n, group, y, stream)
+                               : dequantize_rot_h<8, kSym>(lb, c, scales, nullptr, n, group, y, stream);
 }
 
 }  // namespace fc

@@ -66,6 +66,8 @@ WORKLOADS = {
     "llama3_8b_prefill_sym": Workload("llama3_8b_prefill_sym", 4, 8192, 4096, 8, 8, 128, quantizer="sym"),
     "llama3_70b_prefill_cmeta": Workload("llama3_70b_prefill_cmeta", 4, 8192, 8192, 4, 4, 128, quantizer="cmeta"),
     "llama3_8b_prefill_cmeta": Workload("llama3_8b_prefill_cmeta", 4, 8192, 4096, 8, 8, 128, quantizer="cmeta"),
+    # the rotation table's LLaMA-2-13B row at its group size 1024: hidden 5120 is rotated as five blocks of 1024
+    "llama2_13b_prefill_rot": Workload("llama2_13b_prefill_rot", 4, 8192, 5120, 4, 4, 1024, rotate=True),
 }
 
 

@@ -163,8 +163,11 @@ def test_bench_library_exports_exactly_its_header_and_the_product_library_none_o
 
 def test_rotation_and_stream_reference_argument_checks(L):
     q = L.fc_quantize_rot
-    assert q(P, 4, 1024, 128, 4, 0, P, P, P, None) == -4          # hidden must be 2048, 4096 or 8192
-    assert q(P, 4, 6144, 128, 4, 0, P, P, P, None) == -4
+    # the largest power of two dividing hidden (the rotation's block) must be 1024 ... 8192
+    assert q(P, 4, 512, 128, 4, 0, P, P, P, None) == -4
+    assert q(P, 4, 2560, 128, 4, 0, P, P, P, None) == -4          # 5 x 512
+    assert q(P, 4, 16384, 128, 4, 0, P, P, P, None) == -4
+    assert q(P, 4, 4096 + 128, 128, 4, 0, P, P, P, None) == -4    # block 128
     assert q(P, 4, 4096, 128, 4, 3, P, P, P, None) == -4          # unknown quantizer
     assert q(P, 4, 4096, 128, 4, 2, P, P, P, None) == -2          # FP8 needs 8 bits
     assert q(P, 4, 4096, 128, 4, 0, P, P, None, None) == -1       # asymmetric needs zero-points

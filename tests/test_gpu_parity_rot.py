@@ -16,7 +16,12 @@ QUANTIZERS = [(oracle.ASYM, 4), (oracle.ASYM, 8), (oracle.SYM, 4), (oracle.SYM, 
 
 
 def groups_of(hidden):
-    return [g for g in (32, 128, 1024, 2048, 4096, 8192) if g <= hidden]
+    return [g for g in (32, 128, 1024, 2048, 4096, 8192) if g <= hidden and hidden % g == 0]
+
+
+# power-of-two rows (one block) and rows rotated block by block: 5 x 1024 (the rotation table's LLaMA-2-13B
+# row), 3 x 1024, 7 x 1024, 3 x 2048, 3 x 4096, and a single block of 1024
+HIDDENS = [2048, 4096, 8192, 1024, 5120, 3072, 7168, 6144, 12288]
 
 
 def gpu_quantize_rot(fc, x16, group, bits, quantizer):
@@ -38,8 +43,9 @@ def assert_rot_triplet(got, want, quantizer, what):
 
 
 @pytest.mark.parametrize("quantizer,bits", QUANTIZERS)
-@pytest.mark.parametrize("hidden", [2048, 4096, 8192])
+@pytest.mark.parametrize("hidden", HIDDENS)
 def test_quantize_rot_matches_oracle(fc, quantizer, bits, hidden):
+    # 5 rows: with 1024-element blocks (two to a workgroup) 5 x 5, 5 x 3 and 5 x 7 blocks end in a half-filled chunk
     x = synth_inputs.make_partials(1, 5, hidden, seed=hidden + bits)[0]
     for group in groups_of(hidden):
         want = oracle.quantize_rot(x, group, bits, quantizer)
@@ -70,9 +76,9 @@ def test_quantize_rot_special_rows(fc, hidden):
 
 
 @pytest.mark.parametrize("quantizer,bits", QUANTIZERS)
-@pytest.mark.parametrize("hidden", [2048, 4096, 8192])
+@pytest.mark.parametrize("hidden", HIDDENS)
 def test_dequantize_rot_matches_oracle(fc, quantizer, bits, hidden):
-    x = synth_inputs.make_partials(1, 4, hidden, seed=hidden + 7)[0]
+    x = synth_inputs.make_partials(1, 3, hidden, seed=hidden + 7)[0]
     rng = np.random.default_rng(hidden + bits)
     for group in groups_of(hidden)[::2]:
         c, s, z = oracle.quantize_rot(x, group, bits, quantizer)
@@ -99,7 +105,8 @@ def test_dequantize_rot_matches_oracle(fc, quantizer, bits, hidden):
 @pytest.mark.parametrize("quantizer,bits_rs,bits_ag", [(oracle.ASYM, 4, 4), (oracle.ASYM, 4, 8), (oracle.ASYM, 8, 8),
                                                        (oracle.SYM, 4, 4), (oracle.FP8, 8, 8)])
 def test_allreduce_sim_rot_matches_oracle(fc, quantizer, bits_rs, bits_ag):
-    for n_src, t, hidden, group in ((4, 5, 4096, 128), (2, 3, 8192, 8192), (8, 3, 2048, 2048), (3, 4, 8192, 1024)):
+    for n_src, t, hidden, group in ((4, 5, 4096, 128), (2, 3, 8192, 8192), (8, 3, 2048, 2048), (3, 4, 8192, 1024),
+                                    (4, 7, 5120, 1024), (2, 3, 5120, 128), (3, 1, 1024, 32), (2, 5, 12288, 4096)):
         x = synth_inputs.make_partials(n_src, t, hidden, seed=n_src + hidden)
         want = oracle.allreduce_sim_rot(x, group, bits_rs, bits_ag, quantizer)
         y = Guarded((t, hidden), torch.float16)
@@ -112,7 +119,7 @@ def test_allreduce_sim_rot_matches_oracle(fc, quantizer, bits_rs, bits_ag):
 
 
 def test_rot_rejects_unsupported_rows_and_empty_is_noop(fc):
-    x = torch.zeros((2, 1024), dtype=torch.float16, device="cuda")
+    x = torch.zeros((2, 2560), dtype=torch.float16, device="cuda")           # 5 x 512: blocks below 1024
     with pytest.raises(fc.FcError):
         fc.quantize_rot(x, 128, 4)
     with pytest.raises(fc.FcError):
