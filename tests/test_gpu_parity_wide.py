@@ -278,7 +278,7 @@ def test_randomized_sweep_of_every_quantizer_end_to_end(fc, seed):
         gf = fc.dequant_reduce_requant_cmeta(dev(cm), dev(mm.view(np.int32)), hidden, group, bi, bo)
         wf = oracle.dequant_reduce_requant_cmeta(cm, mm, hidden, group, bi, bo)
         assert same_bits(gf[0].cpu().numpy(), wf[0]) and same_bits(gf[1].cpu().numpy().view(np.uint32), wf[1]), what
-        if hidden in (2048, 4096, 8192):
+        if (hidden & -hidden) in (1024, 2048, 4096, 8192):      # the rotation's block: largest power of two dividing hidden
             q = int(rng.integers(0, 3))
             b8 = (8, 8) if q == 2 else (bi, bo)
             same16(fc.allreduce_sim_rot(xd, group, b8[0], b8[1], q), oracle.allreduce_sim_rot(x, group, b8[0], b8[1], q),
@@ -365,7 +365,7 @@ def test_value_distributions_end_to_end(fc, kind):
         pairs = [("asym", fc.allreduce_sim(xd, group, bi, bo), oracle.allreduce_sim(x, group, bi, bo)),
                  ("sym", fc.allreduce_sim_sym(xd, group, bi, bo), oracle.allreduce_sim_sym(x, group, bi, bo)),
                  ("fp8", fc.allreduce_sim_fp8(xd, group), oracle.allreduce_sim_fp8(x, group))]
-        if hidden in (2048, 4096, 8192):
+        if (hidden & -hidden) in (1024, 2048, 4096, 8192):      # the rotation's block: largest power of two dividing hidden
             q = int(rng.integers(0, 3))
             b = (8, 8) if q == 2 else (bi, bo)
             pairs.append(("rot q=%d" % q, fc.allreduce_sim_rot(xd, group, b[0], b[1], q),
