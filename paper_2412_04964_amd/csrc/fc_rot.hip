@@ -3,17 +3,18 @@
 // quantization: the transform QuaRot applies before quantizing activations).
 //
 // Arithmetic contract (must match include/fc.h): the natural-order
-// Walsh-Hadamard transform over the hidden dimension of one token, evaluated in
-// fp32 as log2(hidden) butterfly stages with spans 1, 2, 4, ... in that order,
-// each butterfly (a, b) -> (a + b, a - b); forward scaling 2^-ceil(n/2), inverse
+// Walsh-Hadamard transform over every aligned block of B = 2^n elements of a
+// token's row, B the largest power of two dividing hidden (the whole row when
+// hidden is a power of two; five blocks of 1024 for hidden 5120), evaluated in
+// fp32 as n butterfly stages with spans 1, 2, 4, ... in that order, each
+// butterfly (a, b) -> (a + b, a - b); forward scaling 2^-ceil(n/2), inverse
 // scaling 2^-floor(n/2).  A butterfly's result does not depend on which thread
 // computes it, so any assignment of butterflies to threads that keeps the stage
 // order is bit-identical.
 //
-// The transform runs over aligned blocks of B = 2^LB elements, B the largest power of two dividing hidden (the
-// whole row when hidden is a power of two; 5 x 1024 for hidden 5120).  Blocks and quantization groups never cross
-// block boundaries, so the tensor is handled as a flat sequence of chunks of 2^LOGH elements (LOGH = LB, except
-// that 1024-element blocks go two to a chunk of 2048).
+// Blocks and quantization groups never cross block boundaries, so the tensor is
+// handled as a flat sequence of chunks of 2^LOGH elements (LOGH = LB = n, except
+// that 1024-element blocks go two to a chunk of 2048 and skip its last stage).
 // One workgroup owns one chunk (2048, 4096 or 8192 elements) and keeps it
 // in registers, R = 16 or 32 values per thread.  The stages over the bits of
 // the index that live inside a thread run in registers; then the row goes to
