@@ -40,6 +40,14 @@ def lib() -> ctypes.CDLL:
             raise ImportError(
                 "%s not found: build it with `python -m paper_2412_04964_amd.build` "
                 "(there is no CPU fallback)" % _LIB_PATH)
+        # PyTorch ships its own copy of the HIP runtime.  The library must bind to the copy that owns the
+        # tensors' device memory, so torch is loaded first: the loader then resolves libfc.so's dependency to
+        # the runtime already in the process instead of bringing in a second one (whose launches on torch's
+        # pointers fail with "no device").
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(_LIB_PATH)
         i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
         L.fc_quantize.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
@@ -485,6 +493,7 @@ def bench_lib() -> ctypes.CDLL:
     if _bench_lib is None:
         if not os.path.exists(_BENCH_LIB_PATH):
             raise ImportError("%s not found: build it with `python -m paper_2412_04964_amd.build`" % _BENCH_LIB_PATH)
+        lib()                                          # torch's HIP runtime first (see lib())
         L = ctypes.CDLL(_BENCH_LIB_PATH)
         L.fc_stream_reference.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p]

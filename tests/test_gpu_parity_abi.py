@@ -240,3 +240,24 @@ def test_one_launch_allreduce_on_both_sides_of_its_size_limit(fc):
         want = oracle.allreduce_sim(x, group, 4, 8).view(np.uint16)
         assert same_bits(got, want), "t=%d: %s" % (t, first_diff(got, want))
         assert same_bits(got, y3)
+
+
+def test_loading_the_library_before_torch_still_shares_torchs_hip_runtime():
+    # a process that touches the package first and torch afterwards: the library must end up on the HIP runtime
+    # that owns torch's device memory (a second copy of the runtime fails every launch with "no device")
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2412_04964_amd as fc\n"
+        "assert fc.version() >= 100\n"                       # loads libfc.so
+        "import torch\n"
+        "x = torch.randn(2, 4, 4096, device='cuda', dtype=torch.float16)\n"
+        "y = fc.allreduce_sim(x, 128, 8, 8)\n"
+        "torch.cuda.synchronize()\n"
+        "assert torch.isfinite(y.float()).all() and (y.float() - x.float().sum(0)).abs().max() < 0.2\n"
+        "print('ok')\n" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
