@@ -26,8 +26,9 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfc.so")
 BENCH_LIB = os.path.join(HERE, "libfc_bench.so")      # measurement aid (include/fc_bench.h), not the product
-# the product library with its fused kernels compiled with -DFC_PLAIN_LANDING_READS (plain, compiler-ordered reads
-# of the landing zones instead of the hand-ordered ones): the GPU tests run the fused cases through both
+# the product library with the kernels that use landing zones (the fused kernels, the one-launch all-reduce) compiled
+# with -DFC_PLAIN_LANDING_READS (plain, compiler-ordered reads of the landing zones instead of the hand-ordered
+# ones): the GPU tests run those cases through both
 PLAIN_LIB = os.path.join(HERE, "libfc_plainreads.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -52,7 +53,9 @@ for _bi in (4, 8):
                       ["-DFC_BITS_IN=%d" % _bi, "-DFC_BITS_OUT=%d" % _bo]))
 
 
-PLAIN_UNITS = [(src, tag + "_plain", defs + ["-DFC_PLAIN_LANDING_READS"]) for src, tag, defs in UNITS if src == "fc_fused.hip"]
+LANDING_SOURCES = ("fc_fused.hip", "fc_sim.hip")
+PLAIN_UNITS = [(src, tag + "_plain", defs + ["-DFC_PLAIN_LANDING_READS"]) for src, tag, defs in UNITS
+               if src in LANDING_SOURCES]
 
 
 def _compile(unit):
@@ -78,7 +81,7 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
                 print(w, file=sys.stderr)
     objs = [o for o, _ in results]
     n_u, n_b = len(UNITS), len(BENCH_UNITS)
-    shared = [o for o, (src, _, _) in zip(objs[:n_u], UNITS) if src != "fc_fused.hip"]
+    shared = [o for o, (src, _, _) in zip(objs[:n_u], UNITS) if src not in LANDING_SOURCES]
     for lib, members in ((LIB, objs[:n_u]), (BENCH_LIB, objs[n_u:n_u + n_b]), (PLAIN_LIB, shared + objs[n_u + n_b:])):
         tmp = lib + ".tmp.%d" % os.getpid()
         cmd = [HIPCC, "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp, *members]

@@ -143,6 +143,12 @@ def plain_lib():
     L.fc_dequant_reduce_requant.restype = i32
     L.fc_dequant_reduce_requant_sym.argtypes = [vp, i64, vp, i64, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     L.fc_dequant_reduce_requant_sym.restype = i32
+    sz = ctypes.c_size_t
+    for name in ("fc_allreduce_sim", "fc_allreduce_sim_sym", "fc_allreduce_sim_cmeta"):
+        getattr(L, name).argtypes = [vp, i32, i64, i64, i32, i32, i32, vp, vp, sz, vp]
+        getattr(L, name).restype = i32
+    L.fc_allreduce_sim_fp8.argtypes = [vp, i32, i64, i64, i32, vp, vp, sz, vp]
+    L.fc_allreduce_sim_fp8.restype = i32
     return L
 
 
@@ -183,6 +189,29 @@ def test_hand_ordered_and_plain_landing_reads_agree_with_the_oracle(fc, plain_li
         torch.cuda.synchronize()
         co.check(); so.check()
         assert same_bits(co.t.cpu().numpy(), want[0]) and same_bits(so.t.cpu().numpy(), want[1]), which + " reads, symmetric"
+
+
+@pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_one_launch_allreduce_with_hand_ordered_and_plain_landing_reads(fc, plain_lib, n_src):
+    # the bandwidth-bound one-launch kernel stages its partials the same way (two loads per source and wavefront)
+    t, h, group = 129, 8192, 128                       # above the limit of the launch-bound kernel
+    x = synth_inputs.make_partials(n_src, t, h, seed=700 + n_src, outlier_frac=0.01)
+    xd = dev(x.view(np.uint16)).view(torch.float16)
+    ws = torch.empty(fc.allreduce_sim_workspace_bytes(n_src, t, h, group, 8, 8), dtype=torch.uint8, device="cuda")
+    cases = [("fc_allreduce_sim", (4, 4), oracle.allreduce_sim(x, group, 4, 4)),
+             ("fc_allreduce_sim_sym", (4, 8), oracle.allreduce_sim_sym(x, group, 4, 8)),
+             ("fc_allreduce_sim_cmeta", (8, 4), oracle.allreduce_sim_cmeta(x, group, 8, 4)),
+             ("fc_allreduce_sim_fp8", (), oracle.allreduce_sim_fp8(x, group))]
+    for which, L in (("hand-ordered", fc.lib()), ("plain", plain_lib)):
+        for name, bits, want in cases:
+            y = Guarded((t, h), torch.float16)
+            rc = getattr(L, name)(xd.data_ptr(), n_src, t, h, group, *bits, y.t.data_ptr(), ws.data_ptr(), ws.numel(),
+                                  _stream())
+            assert rc == 0
+            torch.cuda.synchronize(); y.check()
+            got = y.t.cpu().numpy().view(np.uint16)
+            assert same_bits(got, want.view(np.uint16)), "%s reads, %s N=%d: %s" % (
+                which, name, n_src, first_diff(got, want.view(np.uint16)))
 
 
 # Volumes of at most 2^20 elements per partial with groups of at most 512 elements take fc_allreduce_sim's
