@@ -102,7 +102,7 @@ def assert_f16(got, want, scale_per_elem, what):
     g = got.astype(np.float64); w = want.astype(np.float64)
     tol = 1e-3 * np.maximum(np.abs(w), scale_per_elem)
     fin = np.isfinite(w)
-    assert np.all(np.abs(g - w)[fin] <= tol[fin]), what
+    assert np.all(np.abs(g[fin] - w[fin]) <= tol[fin]), what
     assert same_bits(got.view(np.uint16), want.view(np.uint16)), \
         "%s: %s" % (what, first_diff(got.view(np.uint16), want.view(np.uint16)))
 
