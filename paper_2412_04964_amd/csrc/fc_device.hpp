@@ -54,10 +54,6 @@ constexpr int block_elems(int bits) { return kBlockThreads * lane_elems(bits); }
 // 4-in/1-out copy, up to 3 % on the 8-bit fused kernel).  256-lane groups need 256 threads, the span
 // over which the kernel reduces a group across wavefronts.
 constexpr int fused_block_threads(int lpg) { return (lpg > 0 && lpg <= 128) ? 128 : kBlockThreads; }
-// Launch-bound volumes (at most one wavefront per compute unit of the part): the asymmetric g = 128 instantiations
-// also exist with single-wavefront workgroups, which spreads the work over twice as many compute units and turns the
-// wavefront index into a constant (decode shape: 3.46 -> 3.30 us per launch).
-constexpr int kSmallLaunchWaves = 256;
 // The stand-alone 4-bit quantizer gains the same way (1.8 %); the 8-bit one and the dequantizer do not.
 constexpr int quantize_block_threads(int bits, int lpg) { return (bits == 4 && lpg > 0) ? 128 : kBlockThreads; }
 
@@ -1058,8 +1054,7 @@ __global__ __launch_bounds__(quantize_block_threads(BITS, LPG)) void k_quantize(
 // compile time by the group width (see kEntryMeta below).
 // HM = true: binary16 metadata; scales_in / scales_out are the arrays of 32-bit
 // metadata words and the zeros arrays are not used.
-// BT: threads per workgroup.  Besides the default, the launcher uses single-wavefront workgroups (BT = 64, narrow
-// groups only) for volumes too small to give every compute unit a wavefront.
+// BT: threads per workgroup.
 // WRAP: 0 in the library.  The benchmark aid instantiates WRAP > 0, which makes every workgroup work on tile
 // (its tile % WRAP): the instruction stream of a full launch with its memory traffic confined to a few tiles that
 // stay in the L2, i.e. the time the kernel's arithmetic takes when HBM is out of the picture.
@@ -1074,7 +1069,7 @@ __global__ __launch_bounds__(BT) void k_dequant_reduce_requant(
     constexpr int EPL = lane_elems(BITS_IN);
     constexpr int kWaveElems = 64 * EPL;
     constexpr int kWaves = BT / 64;
-    static_assert(BT == fused_block_threads(LPG) || (BT == 64 && LPG <= 64), "unsupported workgroup size");
+    static_assert(BT == fused_block_threads(LPG), "unsupported workgroup size");
     constexpr int kTileElems = BT * EPL;
     constexpr int kOutBytes = EPL * BITS_OUT / 8;             // code bytes a lane writes: 8, 16 or 32
     static_assert(LPG >= 1 && LPG <= 256 && (LPG & (LPG - 1)) == 0, "lanes per group: a power of two up to 256");

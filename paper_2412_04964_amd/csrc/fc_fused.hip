@@ -2,6 +2,7 @@
 // kernel for one (FC_BITS_IN, FC_BITS_OUT) pair and every fan-in 1..8.
 // Compiled once per pair (the build defines the two macros).
 #include "fc_device.hpp"
+#include "fc_fused_small.hpp"
 #include "fc_launch.hpp"
 
 #if !defined(FC_BITS_IN) || !defined(FC_BITS_OUT)
@@ -40,16 +41,6 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
                 static_cast<uint8_t *>(a.codes_out), a.scales_out, nullptr);
     }
     if (a.codec != CODEC_ASYM) return hipErrorInvalidValue;
-    if constexpr (LPG == 128 / lane_elems(FC_BITS_IN)) {     // g = 128: small volumes in single-wavefront workgroups
-        const int64_t wave_elems = 64 * lane_elems(FC_BITS_IN);
-        const int64_t waves = (a.n_elems + wave_elems - 1) / wave_elems;
-        if (waves <= kSmallLaunchWaves) {
-            return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG, false, 64>, dim3((unsigned)waves), dim3(64), stream,
-                    static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
-                    a.meta_stride, a.n_elems, log2_int(a.group),
-                    static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
-        }
-    }
     return launch_kernel(k_dequant_reduce_requant<FC_BITS_IN, FC_BITS_OUT, NSRC, LPG>, dim3((unsigned)blocks), dim3(BT), stream,
             static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
             a.meta_stride, a.n_elems, log2_int(a.group),
@@ -61,6 +52,15 @@ static hipError_t launch_nl(const FusedArgs &a, hipStream_t stream)
 template <int NSRC>
 static hipError_t launch_n(const FusedArgs &a, hipStream_t stream)
 {
+    // launch-bound volumes (asymmetric quantizer, fp32 metadata): one code word per lane and source
+    if (a.codec == CODEC_ASYM && fused_small_applies(FC_BITS_IN, a.n_elems, a.group)) {
+        const int64_t wave_elems = fused_small_wave_elems(FC_BITS_IN);
+        const int64_t waves = (a.n_elems + wave_elems - 1) / wave_elems;
+        return launch_kernel(k_fused_small<FC_BITS_IN, FC_BITS_OUT, NSRC>, dim3((unsigned)waves), dim3(64), stream,
+                static_cast<const uint8_t *>(a.codes_in), a.codes_stride, a.scales_in, a.zeros_in,
+                a.meta_stride, a.n_elems, log2_int(a.group), a.group / fused_small_lane_elems(FC_BITS_IN),
+                static_cast<uint8_t *>(a.codes_out), a.scales_out, a.zeros_out);
+    }
     switch (a.group / lane_elems(FC_BITS_IN)) {
     case 1: return launch_nl<NSRC, 1>(a, stream);
     case 2: return launch_nl<NSRC, 2>(a, stream);

@@ -71,17 +71,42 @@ def gpu_quantize(fc, x16, group, bits):
     return c.t.cpu().numpy(), s.t.cpu().numpy(), z.t.cpu().numpy()
 
 
+# fc_dequant_reduce_requant has two kernels for the asymmetric quantizer: a launch-bound one (one code word per lane
+# and source) up to 2048 wavefronts of it, i.e. at most 2^20 elements, and the bulk kernel above.  Groups never
+# cross token rows, so repeating the token rows of a case gives the same case at a volume the bulk kernel takes.
+BULK_ELEMS = 1 << 20
+
+
+def bulk_reps(tokens, hidden):
+    return -(-(BULK_ELEMS + 1) // (tokens * hidden))
+
+
+def tile_tokens(a, reps):
+    """repeat the token axis (the last but one) of codes / scales / zero-points / expected outputs"""
+    return np.concatenate([np.asarray(a)] * reps, axis=-2) if reps > 1 else np.asarray(a)
+
+
 def gpu_fused(fc, c, s, z, hidden, group, bits_in, bits_out):
-    t = c.shape[1]
-    co = Guarded((t, hidden * bits_out // 8), torch.uint8)
-    so = Guarded((t, hidden // group), torch.float32)
-    zo = Guarded((t, hidden // group), torch.float32)
-    fc.dequant_reduce_requant(dev(c), dev(s), dev(z), hidden, group, bits_in, bits_out,
-                              out=(co.t, so.t, zo.t))
-    torch.cuda.synchronize()
-    for g in (co, so, zo):
-        g.check()
-    return co.t.cpu().numpy(), so.t.cpu().numpy(), zo.t.cpu().numpy()
+    """the fused step on the case as given and on the case repeated up to the bulk kernel's volumes; both results
+    must be the same bits (the first is returned)"""
+    results = []
+    for reps in (1, bulk_reps(c.shape[1], hidden)):
+        cr, sr, zr = tile_tokens(c, reps), tile_tokens(s, reps), tile_tokens(z, reps)
+        t = cr.shape[1]
+        co = Guarded((t, hidden * bits_out // 8), torch.uint8)
+        so = Guarded((t, hidden // group), torch.float32)
+        zo = Guarded((t, hidden // group), torch.float32)
+        fc.dequant_reduce_requant(dev(cr), dev(sr), dev(zr), hidden, group, bits_in, bits_out,
+                                  out=(co.t, so.t, zo.t))
+        torch.cuda.synchronize()
+        for g in (co, so, zo):
+            g.check()
+        results.append((co.t.cpu().numpy(), so.t.cpu().numpy(), zo.t.cpu().numpy(), reps))
+    small, big = results
+    for name, a, b in zip(("codes", "scales", "zeros"), small[:3], big[:3]):
+        assert same_bits(tile_tokens(a, big[3]), b), "bulk kernel differs from the small-volume call: %s: %s" % (
+            name, first_diff(tile_tokens(a, big[3]), b))
+    return small[:3]
 
 
 def gpu_dequantize(fc, c, s, z, hidden, group, bits):
@@ -235,25 +260,29 @@ def test_fused_adversarial_sums(fc):
 
 
 def test_fused_source_stride_with_padding(fc):
-    # sources separated by more than one slab (stride > slab size)
-    n_src, t, h, group, bits = 3, 4, 2048, 128, 4
-    x = synth_inputs.make_partials(n_src, t, h, seed=9)
-    c, s, z = oracle_stage1(x, group, bits)
-    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits, bits)
-    cp = torch.zeros((n_src, t + 2, h // 2), dtype=torch.uint8, device="cuda")
-    sp = torch.zeros((n_src, t + 1, h // group), dtype=torch.float32, device="cuda")
-    zp = torch.zeros_like(sp)
-    cp[:, :t] = dev(c); sp[:, :t] = dev(s); zp[:, :t] = dev(z)
-    co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
-    so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
-    zo = torch.empty_like(so)
-    rc = fc.lib().fc_dequant_reduce_requant(cp.data_ptr(), cp.stride(0), sp.data_ptr(), zp.data_ptr(),
-                                            sp.stride(0), n_src, t, h, group, bits, bits,
-                                            co.data_ptr(), so.data_ptr(), zo.data_ptr(),
-                                            torch.cuda.current_stream().cuda_stream)
-    assert rc == 0
-    torch.cuda.synchronize()
-    assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "padded stride")
+    # sources separated by more than one slab (stride > slab size), at a launch-bound and at a bulk volume
+    n_src, t0, h, group, bits = 3, 4, 2048, 128, 4
+    x = synth_inputs.make_partials(n_src, t0, h, seed=9)
+    c0, s0, z0 = oracle_stage1(x, group, bits)
+    want0 = oracle.dequant_reduce_requant(c0, s0, z0, h, group, bits, bits)
+    for reps in (1, bulk_reps(t0, h)):
+        c, s, z = tile_tokens(c0, reps), tile_tokens(s0, reps), tile_tokens(z0, reps)
+        want = tuple(tile_tokens(w, reps) for w in want0)
+        t = t0 * reps
+        cp = torch.zeros((n_src, t + 2, h // 2), dtype=torch.uint8, device="cuda")
+        sp = torch.zeros((n_src, t + 1, h // group), dtype=torch.float32, device="cuda")
+        zp = torch.zeros_like(sp)
+        cp[:, :t] = dev(c); sp[:, :t] = dev(s); zp[:, :t] = dev(z)
+        co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
+        so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
+        zo = torch.empty_like(so)
+        rc = fc.lib().fc_dequant_reduce_requant(cp.data_ptr(), cp.stride(0), sp.data_ptr(), zp.data_ptr(),
+                                                sp.stride(0), n_src, t, h, group, bits, bits,
+                                                co.data_ptr(), so.data_ptr(), zo.data_ptr(),
+                                                torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+        torch.cuda.synchronize()
+        assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "padded stride x%d" % reps)
 
 
 def _clamp_case_groups(group, n_groups, rng):
@@ -512,21 +541,26 @@ def test_stream_reference_is_the_xor_of_its_inputs(fc, n_src):
 def test_rank_shares_compose_to_the_whole(fc):
     # sharding by token rows (rank r reduces rows [r T/N, (r+1) T/N) of every source): running the fused
     # kernel once per share, with offset pointers and the full-slab strides, reproduces the single launch
-    n_src, t, h, group, bits = 4, 24, 4096, 128, 4
-    x = synth_inputs.make_partials(n_src, t, h, seed=21)
-    c, s, z = oracle_stage1(x, group, bits)
-    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits, bits)
-    cd, sd, zd = dev(c), dev(s), dev(z)
-    co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
-    so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
-    zo = torch.empty_like(so)
-    share = t // n_src
-    st = torch.cuda.current_stream().cuda_stream
-    for r in range(n_src):
-        r0 = r * share
-        rc = fc.lib().fc_dequant_reduce_requant(
-            cd[0, r0].data_ptr(), cd.stride(0), sd[0, r0].data_ptr(), zd[0, r0].data_ptr(), sd.stride(0),
-            n_src, share, h, group, bits, bits, co[r0].data_ptr(), so[r0].data_ptr(), zo[r0].data_ptr(), st)
-        assert rc == 0
-    torch.cuda.synchronize()
-    assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "row shares")
+    # (shares small enough for the launch-bound kernel, and shares the bulk kernel takes)
+    n_src, t0, h, group, bits = 4, 24, 4096, 128, 4
+    x = synth_inputs.make_partials(n_src, t0, h, seed=21)
+    c0, s0, z0 = oracle_stage1(x, group, bits)
+    want0 = oracle.dequant_reduce_requant(c0, s0, z0, h, group, bits, bits)
+    for reps in (1, n_src * bulk_reps(t0, h)):
+        c, s, z = tile_tokens(c0, reps), tile_tokens(s0, reps), tile_tokens(z0, reps)
+        want = tuple(tile_tokens(w, reps) for w in want0)
+        t = t0 * reps
+        cd, sd, zd = dev(c), dev(s), dev(z)
+        co = torch.empty((t, h // 2), dtype=torch.uint8, device="cuda")
+        so = torch.empty((t, h // group), dtype=torch.float32, device="cuda")
+        zo = torch.empty_like(so)
+        share = t // n_src
+        st = torch.cuda.current_stream().cuda_stream
+        for r in range(n_src):
+            r0 = r * share
+            rc = fc.lib().fc_dequant_reduce_requant(
+                cd[0, r0].data_ptr(), cd.stride(0), sd[0, r0].data_ptr(), zd[0, r0].data_ptr(), sd.stride(0),
+                n_src, share, h, group, bits, bits, co[r0].data_ptr(), so[r0].data_ptr(), zo[r0].data_ptr(), st)
+            assert rc == 0
+        torch.cuda.synchronize()
+        assert_triplet((co.cpu().numpy(), so.cpu().numpy(), zo.cpu().numpy()), want, "row shares x%d" % reps)

@@ -1,13 +1,13 @@
 """Corners of the C ABI on the GPU, called raw through ctypes: per-source metadata slabs that are only
 4-byte aligned (odd source strides), on both ways the fused kernel fetches group parameters (the shared table
-for narrow groups, per-lane loads for wide ones), and the single-wavefront-workgroup launch that small volumes
-take, for every fan-in and bit-width pair.  Bit for bit against the CPU oracle.  Run with ``-m gpu``."""
+for narrow groups, per-lane loads for wide ones), and the launch-bound kernel that small volumes take (one code word
+per lane and source), for every fan-in, bit-width pair and group size, on both sides of its size limit.  Bit for bit against the CPU oracle.  Run with ``-m gpu``."""
 import numpy as np
 import pytest
 
 import oracle
 import synth_inputs
-from test_gpu_parity import Guarded, dev, first_diff, oracle_stage1, same_bits, fc  # noqa: F401
+from test_gpu_parity import Guarded, bulk_reps, dev, first_diff, oracle_stage1, same_bits, tile_tokens, fc  # noqa: F401
 from test_gpu_parity_cmeta import oracle_stage1_cmeta
 
 pytestmark = pytest.mark.gpu
@@ -39,30 +39,36 @@ def _padded_slabs(arrs, stride_elems, dtype, lead):
 def test_fused_with_odd_metadata_strides(fc, group, bits_in, bits_out, n_src):
     # scales and zero-points of source j start at +j*stride floats with an odd stride, so slabs 1, 3, ... are
     # only 4-byte aligned; base pointers stay 16-byte aligned as the header requires
-    t, h = 11, 4096
-    x = synth_inputs.make_partials(n_src, t, h, seed=300 + group + n_src, outlier_frac=0.01)
-    c, s, z = oracle_stage1(x, group, bits_in)
-    want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
-    per = t * h // group
-    for extra in (1, 3, 7):
-        stride = per + extra + (0 if (per + extra) % 2 else 1)            # odd number of floats
-        assert stride % 2 == 1
-        sbuf, sview = _padded_slabs(s, stride, torch.float32, 0)
-        zbuf, zview = _padded_slabs(z, stride, torch.float32, 0)
-        cd = dev(c)
-        co = Guarded((t, h * bits_out // 8), torch.uint8)
-        so = Guarded((t, h // group), torch.float32)
-        zo = Guarded((t, h // group), torch.float32)
-        rc = fc.lib().fc_dequant_reduce_requant(cd.data_ptr(), cd.stride(0), sview.data_ptr(), zview.data_ptr(), stride,
-                                                n_src, t, h, group, bits_in, bits_out, co.t.data_ptr(),
-                                                so.t.data_ptr(), zo.t.data_ptr(), _stream())
-        assert rc == 0
-        torch.cuda.synchronize()
-        for g_ in (co, so, zo):
-            g_.check()
-        for part, got, w_ in zip(("codes", "scales", "zeros"), (co, so, zo), want):
-            assert same_bits(got.t.cpu().numpy(), w_), "stride %d g=%d %s: %s" % (
-                stride, group, part, first_diff(got.t.cpu().numpy(), w_))
+    t0, h = 11, 4096
+    x = synth_inputs.make_partials(n_src, t0, h, seed=300 + group + n_src, outlier_frac=0.01)
+    c0, s0, z0 = oracle_stage1(x, group, bits_in)
+    want0 = oracle.dequant_reduce_requant(c0, s0, z0, h, group, bits_in, bits_out)
+    # the case as it is (narrow groups: the launch-bound kernel) and repeated up to the bulk kernel's volumes, where
+    # narrow groups go through the shared table and wide ones through per-lane loads
+    for reps, extras in ((1, (1, 3, 7)), (bulk_reps(t0, h), (1, 7))):
+        c, s, z = tile_tokens(c0, reps), tile_tokens(s0, reps), tile_tokens(z0, reps)
+        want = tuple(tile_tokens(w, reps) for w in want0)
+        t = t0 * reps
+        per = t * h // group
+        for extra in extras:
+            stride = per + extra + (0 if (per + extra) % 2 else 1)            # odd number of floats
+            assert stride % 2 == 1
+            sbuf, sview = _padded_slabs(s, stride, torch.float32, 0)
+            zbuf, zview = _padded_slabs(z, stride, torch.float32, 0)
+            cd = dev(c)
+            co = Guarded((t, h * bits_out // 8), torch.uint8)
+            so = Guarded((t, h // group), torch.float32)
+            zo = Guarded((t, h // group), torch.float32)
+            rc = fc.lib().fc_dequant_reduce_requant(cd.data_ptr(), cd.stride(0), sview.data_ptr(), zview.data_ptr(),
+                                                    stride, n_src, t, h, group, bits_in, bits_out, co.t.data_ptr(),
+                                                    so.t.data_ptr(), zo.t.data_ptr(), _stream())
+            assert rc == 0
+            torch.cuda.synchronize()
+            for g_ in (co, so, zo):
+                g_.check()
+            for part, got, w_ in zip(("codes", "scales", "zeros"), (co, so, zo), want):
+                assert same_bits(got.t.cpu().numpy(), w_), "x%d stride %d g=%d %s: %s" % (
+                    reps, stride, group, part, first_diff(got.t.cpu().numpy(), w_))
 
 
 @pytest.mark.parametrize("group", [128, 512])
@@ -100,14 +106,15 @@ def test_fused_rejects_misaligned_bases_and_short_strides(fc):
     assert L.fc_dequant_reduce_requant(*args(s.data_ptr(), s.data_ptr(), t * h // g - 1)) == -4      # stride below one slab
 
 
-# The launcher gives asymmetric g = 128 volumes of at most 256 wavefront tiles single-wavefront workgroups:
-# every fan-in and bit-width pair, with a ragged last wavefront tile and rows that straddle tiles
+# Volumes of at most 2048 wavefronts of one 32-bit code word per lane (asymmetric quantizer, groups that fit such a
+# wavefront) take the launch-bound kernel: every fan-in and bit-width pair, with a ragged last wavefront and rows
+# that straddle wavefronts
 @pytest.mark.parametrize("bits_in,bits_out", [(8, 8), (4, 4), (4, 8), (8, 4)])
 @pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_fused_small_volumes_every_fan_in(fc, bits_in, bits_out, n_src):
     for (t, h) in [(7, 2176), (1, 128), (8, 8192), (31, 8192)]:
-        waves = -(-t * h // (64 * 128 // bits_in))
-        assert waves <= 256
+        waves = -(-t * h // (64 * 32 // bits_in))
+        assert waves <= 2048
         x = synth_inputs.make_partials(n_src, t, h, seed=7 * n_src + bits_in + t, outlier_frac=0.02)
         c, s, z = oracle_stage1(x, 128, bits_in)
         want = oracle.dequant_reduce_requant(c, s, z, h, 128, bits_in, bits_out)
@@ -155,12 +162,14 @@ def plain_lib():
 @pytest.mark.parametrize("bits_in,bits_out", [(4, 4), (8, 8), (4, 8), (8, 4)])
 @pytest.mark.parametrize("n_src", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_hand_ordered_and_plain_landing_reads_agree_with_the_oracle(fc, plain_lib, bits_in, bits_out, n_src):
-    t, h = 6, 8192
-    x = synth_inputs.make_partials(n_src, t, h, seed=900 + n_src, outlier_frac=0.01)
+    t0, h = 6, 8192
+    x = synth_inputs.make_partials(n_src, t0, h, seed=900 + n_src, outlier_frac=0.01)
+    reps = bulk_reps(t0, h)                             # the bulk kernel is the one with landing zones
+    t = t0 * reps
     for group in (32, 128, 1024, 8192):
-        c, s, z = oracle_stage1(x, group, bits_in)
-        want = oracle.dequant_reduce_requant(c, s, z, h, group, bits_in, bits_out)
-        cd, sd, zd = dev(c), dev(s), dev(z)
+        c0, s0, z0 = oracle_stage1(x, group, bits_in)
+        want = tuple(tile_tokens(w, reps) for w in oracle.dequant_reduce_requant(c0, s0, z0, h, group, bits_in, bits_out))
+        cd, sd, zd = dev(tile_tokens(c0, reps)), dev(tile_tokens(s0, reps)), dev(tile_tokens(z0, reps))
         for which, L in (("hand-ordered", fc.lib()), ("plain", plain_lib)):
             co = Guarded((t, h * bits_out // 8), torch.uint8)
             so = Guarded((t, h // group), torch.float32)
@@ -174,6 +183,7 @@ def test_hand_ordered_and_plain_landing_reads_agree_with_the_oracle(fc, plain_li
                 got.check()
                 assert same_bits(got.t.cpu().numpy(), w_), "%s reads, N=%d g=%d %d->%d %s: %s" % (
                     which, n_src, group, bits_in, bits_out, part, first_diff(got.t.cpu().numpy(), w_))
+    t = t0
     # symmetric kernels share the staging
     group = 128
     parts = [oracle.quantize_sym(x[j], group, bits_in) for j in range(n_src)]

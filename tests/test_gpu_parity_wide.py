@@ -271,6 +271,12 @@ def test_randomized_sweep_of_every_quantizer_end_to_end(fc, seed):
         same16(fc.allreduce_sim_sym(xd, group, bi, bo), oracle.allreduce_sim_sym(x, group, bi, bo), what + " sym")
         same16(fc.allreduce_sim_fp8(xd, group), oracle.allreduce_sim_fp8(x, group), what + " fp8")
         same16(fc.allreduce_sim_cmeta(xd, group, bi, bo), oracle.allreduce_sim_cmeta(x, group, bi, bo), what + " cmeta")
+        # the asymmetric fused step on its own: the launch-bound kernel at this volume and, with the token rows
+        # repeated, the bulk kernel (gpu_fused runs both and compares them)
+        pa = [oracle.quantize(x[j], group, bi) for j in range(n)]
+        ca = np.stack([p[0] for p in pa]); sa = np.stack([p[1] for p in pa]); za = np.stack([p[2] for p in pa])
+        assert_triplet(gpu_fused(fc, ca, sa, za, hidden, group, bi, bo),
+                       oracle.dequant_reduce_requant(ca, sa, za, hidden, group, bi, bo), what + " fused asym")
         pm = [oracle.quantize_cmeta(x[j], group, bi) for j in range(n)]
         cm = np.stack([p[0] for p in pm]); mm = np.stack([p[1] for p in pm])
         gq = fc.quantize_cmeta(xd[0], group, bi)
