@@ -307,3 +307,12 @@ def test_binding_refuses_tensors_of_another_device(monkeypatch):
     fake = torch.zeros(2, 2, dtype=torch.float16).as_subclass(OnDevice1)
     with pytest.raises(ValueError, match="current device"):
         b._dev(fake, torch.float16, "x")
+
+
+def test_the_user_scripts_import_and_describe_themselves_without_a_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for mod in ("paper_2412_04964_amd.volume_sweep", "paper_2412_04964_amd.ablation"):
+        r = subprocess.run([sys.executable, "-m", mod, "--help"], capture_output=True, text=True, cwd=root, timeout=300)
+        assert r.returncode == 0 and "usage" in r.stdout.lower(), mod + ": " + r.stderr[-500:]

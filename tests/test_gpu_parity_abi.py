@@ -300,3 +300,41 @@ def test_loading_the_library_before_torch_still_shares_torchs_hip_runtime():
         "print('ok')\n" % root)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+
+
+def test_three_entry_points_captured_into_one_graph_at_the_decode_shape(fc):
+    # quantize (all partials in one launch), the launch-bound fused kernel and dequantize captured once, replayed on
+    # new inputs with eager work and synchronizations in between; every replay against the oracle
+    n, t, h, g, b = 8, 8, 8192, 128, 8
+    xd = torch.zeros((n, t, h), dtype=torch.float16, device="cuda")
+    c = torch.empty((n, t, h * b // 8), dtype=torch.uint8, device="cuda")
+    s = torch.empty((n, t, h // g), dtype=torch.float32, device="cuda")
+    z = torch.empty_like(s)
+    co = torch.empty((t, h * b // 8), dtype=torch.uint8, device="cuda")
+    so = torch.empty((t, h // g), dtype=torch.float32, device="cuda")
+    zo = torch.empty_like(so)
+    y = torch.empty((t, h), dtype=torch.float16, device="cuda")
+
+    def chain():
+        fc.quantize(xd.view(n * t, h), g, b, out=(c.view(n * t, -1), s.view(n * t, -1), z.view(n * t, -1)))
+        fc.dequant_reduce_requant(c, s, z, h, g, b, b, out=(co, so, zo))
+        fc.dequantize(co, so, zo, h, g, b, out=y)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()                                                      # every kernel loaded before capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for rep in range(4):
+        x = synth_inputs.make_partials(n, t, h, seed=1200 + rep, outlier_frac=0.01)
+        xd.copy_(dev(x.view(np.uint16)).view(torch.float16))
+        _ = float(xd.float().abs().max())                            # eager work and a synchronization
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.allreduce_sim(x, g, b, b).view(np.uint16)
+        got = y.cpu().numpy().view(np.uint16)
+        assert same_bits(got, want), "replay %d: %s" % (rep, first_diff(got, want))
