@@ -230,3 +230,41 @@ def test_variants_identical_to_their_three_kernel_sequences(fc):
     parts = [fc.quantize_cmeta(xd[j], g, 8) for j in range(n)]
     co, mo = fc.dequant_reduce_requant_cmeta(torch.stack([p[0] for p in parts]), torch.stack([p[1] for p in parts]), h, g, 8, 4)
     check(fc.allreduce_sim_cmeta(xd, g, 8, 4).cpu().numpy(), fc.dequantize_cmeta(co, mo, h, g, 4).cpu().numpy(), "cmeta")
+
+
+@pytest.mark.parametrize("which", ["asym", "sym"])
+def test_volume_beyond_2_to_32_elements(fc, which):
+    # 2^32 + 24576 elements per partial through the one-launch kernel: element indices, the byte offset of the
+    # second partial and the byte offsets inside a partial all pass 2^32; sampled token rows against the oracle
+    # (groups never cross rows)
+    hidden, group, bits = 8192, 128, 4
+    tokens = (1 << 19) + 3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * (1 << 30):
+        pytest.skip("needs 60 GB of free device memory")
+    g = torch.Generator(device="cuda"); g.manual_seed(19)
+    x = torch.empty((2, tokens, hidden), dtype=torch.float16, device="cuda")
+    chunk = 1 << 16
+    for r0 in range(0, tokens, chunk):
+        r1 = min(tokens, r0 + chunk)
+        x[0, r0:r1] = (torch.randn((r1 - r0, hidden), generator=g, device="cuda") * (1.0 + (r0 // chunk) % 3)).half()
+    x[1] = x[0].flip(1) * 0.5
+    y = torch.full((tokens, hidden), 7.0, dtype=torch.float16, device="cuda")
+    L = fc.lib()
+    need = L.fc_allreduce_sim_workspace_bytes(2, tokens, hidden, group, bits, bits)
+    ws = torch.full((need,), 0x5A, dtype=torch.uint8, device="cuda")     # the one-launch kernel leaves it untouched
+    fn = L.fc_allreduce_sim if which == "asym" else L.fc_allreduce_sim_sym
+    rc = fn(x.data_ptr(), 2, tokens, hidden, group, bits, bits, y.data_ptr(), ws.data_ptr(), ws.numel(),
+            torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert bool((ws == 0x5A).all()), "the one-launch kernel wrote to the workspace"
+    marks = [0, 1, (1 << 32) // hidden - 1, (1 << 32) // hidden, (1 << 31) // hidden, (1 << 18) + 1,
+             tokens - 3, tokens - 2, tokens - 1]
+    rows = np.unique(np.array(marks + list(np.random.default_rng(18).integers(0, tokens, 16))))
+    ridx = torch.from_numpy(rows).cuda()
+    xs = x[:, ridx].cpu().numpy()
+    ref = oracle.allreduce_sim if which == "asym" else oracle.allreduce_sim_sym
+    check(y[ridx].cpu().numpy(), ref(xs, group, bits, bits), "rows around 2^32 elements, " + which)
+    # nothing outside the sampled rows is left unwritten: the fill value 7.0 would survive only by accident
+    assert int((y == 7.0).sum().item()) < tokens
