@@ -147,3 +147,32 @@ def test_rot_full_size_on_sampled_rows(fc):
     want = oracle.allreduce_sim_rot(xs, g, w.bits_in, w.bits_out)
     got = y[ridx].cpu().numpy()
     assert same_bits(got.view(np.uint16), want.view(np.uint16)), first_diff(got.view(np.uint16), want.view(np.uint16))
+
+
+@pytest.mark.parametrize("hidden", [8192, 5120])
+def test_rot_volume_beyond_2_to_32_elements(fc, hidden):
+    # element indices and the byte offsets of the input pass 2^32 inside the tensor (for hidden 5120 the blocks of
+    # 1024 also end in a half-filled chunk); sampled token rows against the oracle
+    group, bits = 128, 4
+    tokens = (1 << 32) // hidden + 3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * (1 << 30):
+        pytest.skip("needs 40 GB of free device memory")
+    g = torch.Generator(device="cuda"); g.manual_seed(hidden)
+    x = torch.empty((tokens, hidden), dtype=torch.float16, device="cuda")
+    chunk = 1 << 16
+    for r0 in range(0, tokens, chunk):
+        r1 = min(tokens, r0 + chunk)
+        x[r0:r1] = (torch.randn((r1 - r0, hidden), generator=g, device="cuda") * (1.0 + (r0 // chunk) % 3)).half()
+    c, s, z = fc.quantize_rot(x, group, bits)
+    y = fc.dequantize_rot(c, s, z, hidden, group, bits)
+    torch.cuda.synchronize()
+    marks = [0, 1, (1 << 31) // hidden, (1 << 32) // hidden - 1, (1 << 32) // hidden, tokens - 2, tokens - 1]
+    rows = np.unique(np.array(marks + list(np.random.default_rng(hidden).integers(0, tokens, 12))))
+    ridx = torch.from_numpy(rows).cuda()
+    xs = x[ridx].cpu().numpy()
+    want = oracle.quantize_rot(xs, group, bits, oracle.ASYM)
+    got = (c[ridx].cpu().numpy(), s[ridx].cpu().numpy(), z[ridx].cpu().numpy())
+    assert_rot_triplet(got, want, oracle.ASYM, "rows around 2^32 elements, hidden %d" % hidden)
+    wy = oracle.dequantize_rot(*want, hidden, group, bits, oracle.ASYM)
+    assert same_bits(y[ridx].cpu().numpy().view(np.uint16), wy.view(np.uint16)), "dequantize_rot around 2^32 elements"
